@@ -1,0 +1,197 @@
+/*
+ * kivi.h -- C ABI of the MI355X (gfx950) KIVI decode-attention library.
+ *
+ * The library implements the hot path of KIVI (arXiv 2402.02750): decode-step attention over
+ * a tuning-free asymmetric low-bit KV cache.  Keys are quantised per channel in groups of G
+ * consecutive tokens, values per token in groups of G consecutive channels (Section 3.3), with
+ * zero-point = min and scale = (max - min) / (2^B - 1) (Section 3.1); the most recent tokens stay
+ * in an fp16 residual part (Section 3.3, Algorithm 1).
+ *
+ * Conventions for every entry point
+ *   - returns an int status: KIVI_OK (0) or a negative KIVI_ERR_* code;
+ *   - arguments are validated on the host before anything is enqueued; on error nothing is
+ *     launched and no cache field is changed;
+ *   - work is enqueued on the caller's HIP stream (`stream` is a hipStream_t passed as void*;
+ *     NULL = the default stream) and the call returns without synchronising;
+ *   - the library never allocates or frees memory and keeps no global state: all buffers,
+ *     including the attention workspace, belong to the caller;
+ *   - pointers inside kivi_cache_t, `q`, `out`, `workspace` and the fp16 source tensors are DEVICE
+ *     pointers, 16-byte aligned; the structs themselves and all counts live on the host;
+ *   - every sequence in the batch has the same length (ragged batches are not supported).
+ *
+ * Arithmetic contract of the quantiser (bit-exact between implementations)
+ *   z = min over the group (an fp16 value, stored as is)
+ *   s = fp16_round_nearest_even( (float(max) - float(min)) / float(2^B - 1) )   [fp32 arithmetic]
+ *   code = clamp( round_half_even( (float(x) - float(z)) / float(s) ), 0, 2^B - 1 )   [fp32
+ *          subtract, IEEE fp32 division];  all codes are 0 when s == 0.
+ *   x' = code * s + z.
+ *
+ * Memory layout (all arrays dense, index order as written, b = batch entry, h = kv-head)
+ *   k_codes  uint32 [b][h][cap_q/32][W]   one "key tile" per group of 32 tokens, W = 32*128*B/32
+ *   k_scale  fp16   [b][h][cap_q/32][128]  per (group, channel)
+ *   k_zero   fp16   [b][h][cap_q/32][128]
+ *   v_codes  uint32 [b][h][cap_q/32][W]   one "value tile" per block of 32 tokens
+ *   v_scale  fp16   [b][h][cap_q][4]       per (token, group of 32 channels)
+ *   v_zero   fp16   [b][h][cap_q][4]
+ *   k_resid  fp16   [b][h][cap_r][128]     ring buffer: the i-th oldest residual token is in slot
+ *   v_resid  fp16   [b][h][cap_r][128]     (r_start + i) % cap_r
+ *   q        fp16   [b][n_q_heads][128]
+ *   out      fp32   [b][n_q_heads][128]
+ *
+ *   A code tile covers 32 tokens x 128 channels and is addressed by (u, lane, e), u in [0,8),
+ *   lane in [0,64), e in [0,8):
+ *     key tile  : token   = (u & 1) * 16 + (lane & 15),  channel = (u >> 1) * 32 + (lane >> 4) * 8 + e
+ *     value tile: channel = u * 16 + (lane & 15),         token   = (lane >> 4) * 8 + e
+ *     B = 2 : word = lane*4 + (u >> 1),                         bit = (e & 1)*16 + 2*((u & 1)*4 + (e >> 1))
+ *     B = 4 : i = (u >> 1)*2 + (e >> 2), word = (i >> 2)*256 + lane*4 + (i & 3),
+ *                                                               bit = (e & 1)*16 + 4*((u & 1)*2 + ((e >> 1) & 1))
+ *   (little-endian uint32 words).  The layout hands wavefront lane `lane` one 16-byte piece per
+ *   256-word plane that already is its operand fragment of a 16x16x32 matrix instruction.
+ */
+#ifndef KIVI_H
+#define KIVI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KIVI_OK                 0
+#define KIVI_ERR_INVALID_ARG   -1   /* null/misaligned pointer, inconsistent counts, capacity exceeded */
+#define KIVI_ERR_UNSUPPORTED   -2   /* a shape or mode this build has no kernel for                   */
+#define KIVI_ERR_WORKSPACE     -3   /* workspace missing or smaller than kivi_decode_workspace_bytes  */
+#define KIVI_ERR_HIP           -4   /* the HIP runtime reported a launch error                        */
+
+/* residual-flush policies for kivi_flush_residual */
+#define KIVI_FLUSH_WINDOW       0   /* quantise the oldest G tokens of K and V while the fp16 window
+                                       holds >= R + G tokens: the most recent R tokens stay fp16      */
+#define KIVI_FLUSH_ALG1         1   /* Algorithm 1 (Decoding) literally: the whole key residual when it
+                                       holds exactly R tokens; the oldest value tokens beyond R       */
+
+/* decode kernel families (kivi_layout_t.decode_path) */
+#define KIVI_DECODE_AUTO        0
+#define KIVI_DECODE_VALU        1   /* vector-ALU dot products + cross-lane reductions               */
+#define KIVI_DECODE_MFMA        2   /* codes fed to the matrix cores as exact fp16                   */
+
+/* Static description of one attention layer's cache (host struct). */
+typedef struct kivi_layout {
+    int32_t batch;          /* b                                                          */
+    int32_t n_q_heads;      /* query heads; must be a multiple of n_kv_heads              */
+    int32_t n_kv_heads;     /* key/value heads                                            */
+    int32_t head_dim;       /* D; this build supports 128                                 */
+    int32_t bits;           /* B: 2 or 4                                                  */
+    int32_t group;          /* G: this build supports 32                                  */
+    int32_t residual;       /* R: residual length, a multiple of G (Section 3.3)          */
+    int32_t cap_q_tokens;   /* capacity of the quantised part in tokens, multiple of 32   */
+    int32_t cap_r_tokens;   /* capacity of each fp16 ring in tokens, multiple of 32, >= R + G */
+    int32_t decode_path;    /* KIVI_DECODE_*                                              */
+} kivi_layout_t;
+
+/* One layer's cache: the 4-tuple (Q(X_Kg), X_Kr, Q(X_Vg), X_Vr) of Algorithm 1.
+ * The pointers are the caller's device buffers (sizes: kivi_cache_sizes); the integers are host
+ * state that the library reads and advances. */
+typedef struct kivi_cache {
+    void *k_codes, *k_scale, *k_zero;
+    void *v_codes, *v_scale, *v_zero;
+    void *k_resid, *v_resid;
+    int32_t n_kq;        /* quantised key tokens, multiple of G        */
+    int32_t n_vq;        /* quantised value tokens                     */
+    int32_t k_r_start;   /* ring slot of the oldest residual key       */
+    int32_t n_kr;        /* residual key tokens                        */
+    int32_t v_r_start;   /* ring slot of the oldest residual value     */
+    int32_t n_vr;        /* residual value tokens                      */
+} kivi_cache_t;
+
+/* Byte sizes of the eight cache buffers for a layout. */
+typedef struct kivi_cache_sizes {
+    size_t k_codes, k_scale, k_zero, v_codes, v_scale, v_zero, k_resid, v_resid;
+} kivi_cache_sizes_t;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* kivi_status_string(int status);
+
+/* Host helper: buffer sizes for `layout`.  Errors: INVALID_ARG, UNSUPPORTED. */
+int kivi_cache_sizes(const kivi_layout_t* layout, kivi_cache_sizes_t* sizes);
+
+/* Host helper: bytes of workspace kivi_decode_attention needs for ANY cache state that fits
+ * `layout` (partial softmax statistics and outputs of the context splits). */
+int kivi_decode_workspace_bytes(const kivi_layout_t* layout, size_t* bytes);
+
+/*
+ * Key quantisation, per channel in groups of G tokens -- Section 3.3 "Algorithm" and
+ * Algorithm 1 (KeyQuant: GroupQuant(X_Kg, dim=channel)); formula of Section 3.1.
+ *   k_fp16     device, fp16, element (b, h, t, c) at k_fp16[b*stride_b + h*stride_h + t*stride_t + c]
+ *              (strides in elements, multiples of 8)
+ *   n_tokens   number of tokens to quantise, a multiple of G; they become groups
+ *              n_kq/G ... of the cache, and cache->n_kq advances by n_tokens.
+ * Errors: INVALID_ARG (null, misaligned, n_tokens % G != 0, capacity), UNSUPPORTED, HIP.
+ */
+int kivi_quantize_key_groups(const kivi_layout_t* layout, const void* k_fp16, int64_t stride_b,
+                             int64_t stride_h, int64_t stride_t, int32_t n_tokens,
+                             kivi_cache_t* cache, void* stream);
+
+/*
+ * Value quantisation, per token in groups of G channels -- Section 3.3 and Algorithm 1
+ * (GroupQuant(X_Vg, dim=token, numGroup=d//G)); formula of Section 3.1.
+ * Same argument meaning as above; the tokens are appended at cache->n_vq, which advances.
+ * n_tokens need not be a multiple of 32: a partly filled value tile is completed by later calls.
+ */
+int kivi_quantize_value_tokens(const kivi_layout_t* layout, const void* v_fp16, int64_t stride_b,
+                               int64_t stride_h, int64_t stride_t, int32_t n_tokens,
+                               kivi_cache_t* cache, void* stream);
+
+/*
+ * Prefill -- Algorithm 1 (Prefill): split the prompt's keys and values into the grouped part,
+ * which is quantised, and the fp16 residual part, which is copied into the rings.  The cache must
+ * be empty (all counters 0).  `policy` selects the split:
+ *   KIVI_FLUSH_WINDOW  K and V alike: the first floor(max(l - R, 0) / G) * G tokens are quantised;
+ *   KIVI_FLUSH_ALG1    keys: l - l % R tokens (KeyQuant); values: max(l - R, 0) tokens.
+ * Source tensors as for kivi_quantize_key_groups (separate strides for K and V).
+ */
+int kivi_prefill(const kivi_layout_t* layout, const void* k_fp16, int64_t k_stride_b, int64_t k_stride_h,
+                 int64_t k_stride_t, const void* v_fp16, int64_t v_stride_b, int64_t v_stride_h,
+                 int64_t v_stride_t, int32_t n_tokens, int32_t policy, kivi_cache_t* cache, void* stream);
+
+/*
+ * Append the new token's key and value to the fp16 residual parts -- Algorithm 1 (Decoding):
+ * X_Kr <- Concat(X_Kr, t_K), X_Vr <- Concat(X_Vr, t_V).
+ *   k_new, v_new   device, fp16 [b][n_kv_heads][128]
+ * Errors: INVALID_ARG (null, a ring is full: flush first).
+ */
+int kivi_append_residual(const kivi_layout_t* layout, kivi_cache_t* cache, const void* k_new,
+                         const void* v_new, void* stream);
+
+/*
+ * Move the oldest residual tokens into the quantised part -- Section 3.3 ("once X_Kr reaches R
+ * tokens ... we quantize and concatenate it"; the value queue) and Algorithm 1 (Decoding).
+ * `policy` is KIVI_FLUSH_WINDOW or KIVI_FLUSH_ALG1 (see above).  A call that finds nothing to
+ * flush enqueues nothing.  On return the cache counters describe the new split.
+ * Optional outputs (host, may be NULL): number of key / value tokens quantised by this call.
+ */
+int kivi_flush_residual(const kivi_layout_t* layout, kivi_cache_t* cache, int32_t policy,
+                        int32_t* n_key_flushed, int32_t* n_value_flushed, void* stream);
+
+/*
+ * Decode-step attention over the mixed-precision cache -- Equation 4 (tiled logits over the
+ * quantised and the residual keys), Equation 1 / Algorithm 1 (Decoding): softmax over the
+ * concatenated logits, t_O = A_g Q(X_Vg) + A_r X_Vr.
+ *   q              device, fp16 [b][n_q_heads][128]; query head j reads kv-head
+ *                  j / (n_q_heads / n_kv_heads)
+ *   softmax_scale  multiplies the logits before the softmax (1/sqrt(D) for the usual attention)
+ *   out            device, fp32 [b][n_q_heads][128]
+ *   workspace      device scratch of at least kivi_decode_workspace_bytes(layout) bytes; contents
+ *                  need not be initialised and are undefined afterwards
+ * Requires n_kq + n_kr == n_vq + n_vr >= 1.  The K and V splits may differ (Algorithm 1 splits
+ * them differently).
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.
+ */
+int kivi_decode_attention(const kivi_layout_t* layout, const kivi_cache_t* cache, const void* q,
+                          float softmax_scale, float* out, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KIVI_H */

@@ -1,0 +1,313 @@
+// Host side of the C ABI (include/kivi.h): argument validation, split planning, launches.
+// No allocation, no global state, no synchronisation.
+#include "kivi_internal.h"
+
+#include <algorithm>
+
+namespace kivi {
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_layout(const kivi_layout_t* l) {
+    if (!l) return KIVI_ERR_INVALID_ARG;
+    if (l->batch < 1 || l->n_q_heads < 1 || l->n_kv_heads < 1) return KIVI_ERR_INVALID_ARG;
+    if (l->batch > 65535 || l->n_kv_heads > 65535) return KIVI_ERR_INVALID_ARG;
+    if (l->n_q_heads % l->n_kv_heads != 0) return KIVI_ERR_INVALID_ARG;
+    if (l->residual < 0 || l->cap_q_tokens < 0 || l->cap_r_tokens < 0) return KIVI_ERR_INVALID_ARG;
+    if (l->decode_path < KIVI_DECODE_AUTO || l->decode_path > KIVI_DECODE_MFMA) return KIVI_ERR_INVALID_ARG;
+    if (l->head_dim != kHeadDim) return KIVI_ERR_UNSUPPORTED;
+    if (l->bits != 2 && l->bits != 4) return KIVI_ERR_UNSUPPORTED;
+    if (l->group != kTileTokens) return KIVI_ERR_UNSUPPORTED;
+    if (l->residual % l->group != 0) return KIVI_ERR_INVALID_ARG;          // Section 3.3: G | R
+    if (l->cap_q_tokens % kTileTokens != 0 || l->cap_r_tokens % kTileTokens != 0) return KIVI_ERR_INVALID_ARG;
+    if (l->cap_r_tokens < l->residual + l->group) return KIVI_ERR_INVALID_ARG;
+    const int rep = l->n_q_heads / l->n_kv_heads;
+    if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return KIVI_ERR_UNSUPPORTED;
+    return KIVI_OK;
+}
+
+int check_cache(const kivi_layout_t* l, const kivi_cache_t* c) {
+    if (!c) return KIVI_ERR_INVALID_ARG;
+    const void* ptrs[8] = {c->k_codes, c->k_scale, c->k_zero, c->v_codes,
+                           c->v_scale, c->v_zero, c->k_resid, c->v_resid};
+    for (const void* p : ptrs)
+        if (!p || !aligned16(p)) return KIVI_ERR_INVALID_ARG;
+    if (c->n_kq < 0 || c->n_vq < 0 || c->n_kr < 0 || c->n_vr < 0) return KIVI_ERR_INVALID_ARG;
+    if (c->n_kq % l->group != 0) return KIVI_ERR_INVALID_ARG;
+    if (c->n_kq > l->cap_q_tokens || c->n_vq > l->cap_q_tokens) return KIVI_ERR_INVALID_ARG;
+    if (c->n_kr > l->cap_r_tokens || c->n_vr > l->cap_r_tokens) return KIVI_ERR_INVALID_ARG;
+    if (c->k_r_start < 0 || c->k_r_start >= l->cap_r_tokens) return KIVI_ERR_INVALID_ARG;
+    if (c->v_r_start < 0 || c->v_r_start >= l->cap_r_tokens) return KIVI_ERR_INVALID_ARG;
+    return KIVI_OK;
+}
+
+int check_source(const void* x, int64_t sb, int64_t sh, int64_t st) {
+    if (!x || !aligned16(x)) return KIVI_ERR_INVALID_ARG;
+    if (sb < 0 || sh < 0 || st < kHeadDim) return KIVI_ERR_INVALID_ARG;
+    if ((sb | sh | st) & 7) return KIVI_ERR_INVALID_ARG;          // keeps every row 16-byte aligned
+    return KIVI_OK;
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Upper bound of the number of context splits for any cache state of this layout.
+int max_splits(const kivi_layout_t* l) {
+    const int tiles = (l->cap_q_tokens + l->cap_r_tokens) / kTileTokens + 1;
+    return tiles;   // every split covers at least one tile
+}
+
+SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c) {
+    SplitPlan s{};
+    const int length = c->n_kq + c->n_kr;
+    s.tiles_a = std::min(c->n_kq, c->n_vq) / kTileTokens;
+    s.tiles_total = ceil_div(length, kTileTokens);
+    // Aim at ~16 workgroups per compute unit in flight over the whole grid so the 256 CUs stay
+    // busy through the tail, but keep splits long enough that the per-split partial results
+    // (520 B per query head) stay a small fraction of the bytes a split streams.
+    const int64_t units = (int64_t)l->batch * l->n_kv_heads;
+    const int64_t target_wgs = 4096;
+    const int rep = l->n_q_heads / l->n_kv_heads;
+    int tps = (int)std::min<int64_t>(kMaxSplitTiles, ((int64_t)s.tiles_a * units + target_wgs - 1) / target_wgs);
+    tps = std::max(tps, std::min(kMaxSplitTiles, 4 * rep));
+    s.tiles_per_split_a = std::max(1, std::min(tps, kMaxSplitTiles));
+    // fp16 rows cost 512 B per token against 96 B (2-bit) or 160 B (4-bit)
+    const int packed_per_tile = kTileTokens * 2 * (kHeadDim * l->bits / 8 + 16);
+    const int fp16_per_tile = kTileTokens * 2 * kHeadDim * 2;
+    s.tiles_per_split_b = std::max(1, std::min(8, s.tiles_per_split_a * packed_per_tile / fp16_per_tile));
+    s.n_splits_a = ceil_div(s.tiles_a, s.tiles_per_split_a);
+    s.n_splits_b = ceil_div(s.tiles_total - s.tiles_a, s.tiles_per_split_b);
+    return s;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? KIVI_OK : KIVI_ERR_HIP; }
+
+int enqueue_key_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens,
+                      hipStream_t hs) {
+    QuantKeyParams p{};
+    p.src = src;
+    p.codes = static_cast<uint32_t*>(c->k_codes);
+    p.scale = static_cast<__half*>(c->k_scale);
+    p.zero = static_cast<__half*>(c->k_zero);
+    p.n_kv_heads = l->n_kv_heads; p.cap_tiles = l->cap_q_tokens / kTileTokens; p.bits = l->bits;
+    p.first_tile = c->n_kq / kTileTokens; p.n_tiles = n_tokens / kTileTokens; p.batch = l->batch;
+    return hip_status(launch_quantize_keys(p, hs));
+}
+
+int enqueue_value_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens,
+                        hipStream_t hs) {
+    QuantValueParams p{};
+    p.src = src;
+    p.codes = static_cast<uint32_t*>(c->v_codes);
+    p.scale = static_cast<__half*>(c->v_scale);
+    p.zero = static_cast<__half*>(c->v_zero);
+    p.n_kv_heads = l->n_kv_heads; p.cap_tiles = l->cap_q_tokens / kTileTokens; p.bits = l->bits;
+    p.first_token = c->n_vq; p.n_tokens = n_tokens; p.batch = l->batch;
+    return hip_status(launch_quantize_values(p, hs));
+}
+
+}  // namespace
+}  // namespace kivi
+
+using namespace kivi;
+
+extern "C" {
+
+const char* kivi_status_string(int status) {
+    switch (status) {
+        case KIVI_OK: return "KIVI_OK";
+        case KIVI_ERR_INVALID_ARG: return "KIVI_ERR_INVALID_ARG";
+        case KIVI_ERR_UNSUPPORTED: return "KIVI_ERR_UNSUPPORTED";
+        case KIVI_ERR_WORKSPACE: return "KIVI_ERR_WORKSPACE";
+        case KIVI_ERR_HIP: return "KIVI_ERR_HIP";
+        default: return "KIVI_ERR_UNKNOWN";
+    }
+}
+
+int kivi_cache_sizes(const kivi_layout_t* l, kivi_cache_sizes_t* out) {
+    if (int st = check_layout(l)) return st;
+    if (!out) return KIVI_ERR_INVALID_ARG;
+    const size_t units = (size_t)l->batch * l->n_kv_heads;
+    const size_t tiles = (size_t)l->cap_q_tokens / kTileTokens;
+    const size_t words = (size_t)kTileTokens * kHeadDim * l->bits / 32;
+    out->k_codes = out->v_codes = units * tiles * words * 4;
+    out->k_scale = out->k_zero = units * tiles * kHeadDim * 2;
+    out->v_scale = out->v_zero = units * (size_t)l->cap_q_tokens * (kHeadDim / kTileTokens) * 2;
+    out->k_resid = out->v_resid = units * (size_t)l->cap_r_tokens * kHeadDim * 2;
+    return KIVI_OK;
+}
+
+int kivi_decode_workspace_bytes(const kivi_layout_t* l, size_t* bytes) {
+    if (int st = check_layout(l)) return st;
+    if (!bytes) return KIVI_ERR_INVALID_ARG;
+    const size_t rows = (size_t)l->batch * l->n_q_heads * max_splits(l);
+    *bytes = rows * (kHeadDim + 2) * sizeof(float);
+    return KIVI_OK;
+}
+
+int kivi_quantize_key_groups(const kivi_layout_t* l, const void* k, int64_t sb, int64_t sh, int64_t st,
+                             int32_t n_tokens, kivi_cache_t* c, void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    if (int s = check_source(k, sb, sh, st)) return s;
+    if (n_tokens < 0 || n_tokens % l->group != 0) return KIVI_ERR_INVALID_ARG;
+    if ((int64_t)c->n_kq + n_tokens > l->cap_q_tokens) return KIVI_ERR_INVALID_ARG;
+    if (n_tokens == 0) return KIVI_OK;
+    const RowSource src{static_cast<const __half*>(k), sb, sh, st, 0, 0};
+    if (int s = enqueue_key_quant(l, c, src, n_tokens, static_cast<hipStream_t>(stream))) return s;
+    c->n_kq += n_tokens;
+    return KIVI_OK;
+}
+
+int kivi_quantize_value_tokens(const kivi_layout_t* l, const void* v, int64_t sb, int64_t sh, int64_t st,
+                               int32_t n_tokens, kivi_cache_t* c, void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    if (int s = check_source(v, sb, sh, st)) return s;
+    if (n_tokens < 0) return KIVI_ERR_INVALID_ARG;
+    if ((int64_t)c->n_vq + n_tokens > l->cap_q_tokens) return KIVI_ERR_INVALID_ARG;
+    if (n_tokens == 0) return KIVI_OK;
+    const RowSource src{static_cast<const __half*>(v), sb, sh, st, 0, 0};
+    if (int s = enqueue_value_quant(l, c, src, n_tokens, static_cast<hipStream_t>(stream))) return s;
+    c->n_vq += n_tokens;
+    return KIVI_OK;
+}
+
+int kivi_append_residual(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new, const void* v_new,
+                         void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return KIVI_ERR_INVALID_ARG;
+    if (c->n_kr >= l->cap_r_tokens || c->n_vr >= l->cap_r_tokens) return KIVI_ERR_INVALID_ARG;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int64_t sh = kHeadDim, sb = sh * l->n_kv_heads;
+    CopyRowsParams p{};
+    p.stride_b = sb; p.stride_h = sh; p.stride_t = kHeadDim; p.src_t0 = 0;
+    p.cap_r = l->cap_r_tokens; p.n_tokens = 1; p.n_kv_heads = l->n_kv_heads; p.batch = l->batch;
+    p.src = static_cast<const __half*>(k_new); p.dst = static_cast<__half*>(c->k_resid);
+    p.dst_slot0 = (c->k_r_start + c->n_kr) % l->cap_r_tokens;
+    if (int s = hip_status(launch_copy_rows(p, hs))) return s;
+    p.src = static_cast<const __half*>(v_new); p.dst = static_cast<__half*>(c->v_resid);
+    p.dst_slot0 = (c->v_r_start + c->n_vr) % l->cap_r_tokens;
+    if (int s = hip_status(launch_copy_rows(p, hs))) return s;
+    c->n_kr += 1;
+    c->n_vr += 1;
+    return KIVI_OK;
+}
+
+int kivi_flush_residual(const kivi_layout_t* l, kivi_cache_t* c, int32_t policy, int32_t* n_key_flushed,
+                        int32_t* n_value_flushed, void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    if (policy != KIVI_FLUSH_WINDOW && policy != KIVI_FLUSH_ALG1) return KIVI_ERR_INVALID_ARG;
+    const int G = l->group, R = l->residual;
+    int nk = 0, nv = 0;
+    if (policy == KIVI_FLUSH_WINDOW) {
+        if (c->n_kr != c->n_vr || c->n_kq != c->n_vq) return KIVI_ERR_INVALID_ARG;   // symmetric policy
+        while (c->n_kr - nk >= R + G) nk += G;
+        nv = nk;
+    } else {
+        if (R > 0 && c->n_kr == R) nk = R;                 // Algorithm 1: len(X_Kr) == R
+        if (c->n_vr > R) nv = c->n_vr - R;                 // Algorithm 1: len(X_Vr) > R
+    }
+    if ((int64_t)c->n_kq + nk > l->cap_q_tokens || (int64_t)c->n_vq + nv > l->cap_q_tokens)
+        return KIVI_ERR_INVALID_ARG;
+    const int64_t sh = (int64_t)l->cap_r_tokens * kHeadDim, sb = sh * l->n_kv_heads;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (nk > 0) {
+        const RowSource src{static_cast<const __half*>(c->k_resid), sb, sh, kHeadDim, c->k_r_start, l->cap_r_tokens};
+        if (int s = enqueue_key_quant(l, c, src, nk, hs)) return s;
+    }
+    if (nv > 0) {
+        const RowSource src{static_cast<const __half*>(c->v_resid), sb, sh, kHeadDim, c->v_r_start, l->cap_r_tokens};
+        if (int s = enqueue_value_quant(l, c, src, nv, hs)) return s;
+    }
+    c->n_kq += nk; c->n_kr -= nk; c->k_r_start = (c->k_r_start + nk) % l->cap_r_tokens;
+    c->n_vq += nv; c->n_vr -= nv; c->v_r_start = (c->v_r_start + nv) % l->cap_r_tokens;
+    if (n_key_flushed) *n_key_flushed = nk;
+    if (n_value_flushed) *n_value_flushed = nv;
+    return KIVI_OK;
+}
+
+int kivi_prefill(const kivi_layout_t* l, const void* k, int64_t ksb, int64_t ksh, int64_t kst, const void* v,
+                 int64_t vsb, int64_t vsh, int64_t vst, int32_t n_tokens, int32_t policy, kivi_cache_t* c,
+                 void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    if (int s = check_source(k, ksb, ksh, kst)) return s;
+    if (int s = check_source(v, vsb, vsh, vst)) return s;
+    if (policy != KIVI_FLUSH_WINDOW && policy != KIVI_FLUSH_ALG1) return KIVI_ERR_INVALID_ARG;
+    if (n_tokens < 0 || c->n_kq || c->n_vq || c->n_kr || c->n_vr) return KIVI_ERR_INVALID_ARG;
+    const int G = l->group, R = l->residual;
+    int nkq, nvq;
+    if (policy == KIVI_FLUSH_WINDOW) {
+        nkq = nvq = std::max(n_tokens - R, 0) / G * G;
+    } else {
+        nkq = R > 0 ? n_tokens - n_tokens % R : n_tokens / G * G;   // KeyQuant: r = l % R
+        nvq = std::max(n_tokens - R, 0);                            // X_Vg = X_V[:l - R]
+    }
+    const int nkr = n_tokens - nkq, nvr = n_tokens - nvq;
+    if (nkq > l->cap_q_tokens || nvq > l->cap_q_tokens || nkr > l->cap_r_tokens || nvr > l->cap_r_tokens)
+        return KIVI_ERR_INVALID_ARG;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (nkq > 0) {
+        const RowSource src{static_cast<const __half*>(k), ksb, ksh, kst, 0, 0};
+        if (int s = enqueue_key_quant(l, c, src, nkq, hs)) return s;
+    }
+    if (nvq > 0) {
+        const RowSource src{static_cast<const __half*>(v), vsb, vsh, vst, 0, 0};
+        if (int s = enqueue_value_quant(l, c, src, nvq, hs)) return s;
+    }
+    CopyRowsParams p{};
+    p.cap_r = l->cap_r_tokens; p.n_kv_heads = l->n_kv_heads; p.batch = l->batch; p.dst_slot0 = 0;
+    p.src = static_cast<const __half*>(k); p.stride_b = ksb; p.stride_h = ksh; p.stride_t = kst;
+    p.src_t0 = nkq; p.n_tokens = nkr; p.dst = static_cast<__half*>(c->k_resid);
+    if (int s = hip_status(launch_copy_rows(p, hs))) return s;
+    p.src = static_cast<const __half*>(v); p.stride_b = vsb; p.stride_h = vsh; p.stride_t = vst;
+    p.src_t0 = nvq; p.n_tokens = nvr; p.dst = static_cast<__half*>(c->v_resid);
+    if (int s = hip_status(launch_copy_rows(p, hs))) return s;
+    c->n_kq = nkq; c->n_vq = nvq; c->n_kr = nkr; c->n_vr = nvr; c->k_r_start = 0; c->v_r_start = 0;
+    return KIVI_OK;
+}
+
+int kivi_decode_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, float softmax_scale,
+                          float* out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    if (!q || !out || !aligned16(q) || !aligned16(out)) return KIVI_ERR_INVALID_ARG;
+    const int length = c->n_kq + c->n_kr;
+    if (length < 1 || length != c->n_vq + c->n_vr) return KIVI_ERR_INVALID_ARG;
+    size_t need = 0;
+    kivi_decode_workspace_bytes(l, &need);
+    if (!workspace || !aligned16(workspace) || workspace_bytes < need) return KIVI_ERR_WORKSPACE;
+
+    DecodeParams p{};
+    p.k_codes = static_cast<const uint32_t*>(c->k_codes);
+    p.k_scale = static_cast<const __half*>(c->k_scale);
+    p.k_zero = static_cast<const __half*>(c->k_zero);
+    p.v_codes = static_cast<const uint32_t*>(c->v_codes);
+    p.v_scale = static_cast<const __half*>(c->v_scale);
+    p.v_zero = static_cast<const __half*>(c->v_zero);
+    p.k_resid = static_cast<const __half*>(c->k_resid);
+    p.v_resid = static_cast<const __half*>(c->v_resid);
+    p.n_kq = c->n_kq; p.n_vq = c->n_vq; p.k_r_start = c->k_r_start; p.n_kr = c->n_kr;
+    p.v_r_start = c->v_r_start; p.n_vr = c->n_vr;
+    p.cap_tiles = l->cap_q_tokens / kTileTokens; p.cap_r = l->cap_r_tokens;
+    p.q = static_cast<const __half*>(q); p.out = out;
+    p.softmax_scale = softmax_scale;
+    p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
+    p.length = length;
+    p.plan = plan_splits(l, c);
+    const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
+    p.part_o = static_cast<float*>(workspace);
+    p.part_ml = p.part_o + rows * kHeadDim;
+
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int path = l->decode_path == KIVI_DECODE_AUTO ? KIVI_DECODE_VALU : l->decode_path;
+    hipError_t e = path == KIVI_DECODE_MFMA ? launch_decode_mfma(p, hs) : launch_decode_valu(p, hs);
+    if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
+    if (int s = hip_status(e)) return s;
+    return hip_status(launch_merge(p, hs));
+}
+
+}  // extern "C"

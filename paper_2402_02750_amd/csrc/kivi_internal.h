@@ -1,0 +1,93 @@
+// Internal declarations shared by the library's translation units (host side only).
+// Nothing here is part of the ABI; see include/kivi.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "kivi.h"
+
+namespace kivi {
+
+constexpr int kHeadDim = 128;
+constexpr int kTileTokens = 32;        // tokens per code tile == supported group size G
+constexpr int kMaxSplitTiles = 32;     // a context split covers at most 32 tiles (1024 tokens)
+constexpr int kMaxRep = 8;             // query heads per kv-head handled by one workgroup pass
+
+// Source of fp16 rows for the quantise kernels: either a strided tensor or a ring buffer.
+struct RowSource {
+    const __half* base;   // element (b, h, t, c) at base[b*stride_b + h*stride_h + slot(t)*stride_t + c]
+    int64_t stride_b, stride_h, stride_t;
+    int32_t ring_start;   // slot(t) = (ring_start + t) % ring_cap when ring_cap > 0, else t
+    int32_t ring_cap;
+};
+
+struct QuantKeyParams {
+    RowSource src;
+    uint32_t* codes;      // [b][h][cap_tiles][W]
+    __half* scale;        // [b][h][cap_tiles][128]
+    __half* zero;
+    int32_t n_kv_heads, cap_tiles, bits;
+    int32_t first_tile;   // destination tile index of source token 0
+    int32_t n_tiles;
+    int32_t batch;
+};
+
+struct QuantValueParams {
+    RowSource src;
+    uint32_t* codes;      // [b][h][cap_tiles][W]
+    __half* scale;        // [b][h][cap_tokens][4]
+    __half* zero;
+    int32_t n_kv_heads, cap_tiles, bits;
+    int32_t first_token;  // destination token index of source token 0 (any value)
+    int32_t n_tokens;
+    int32_t batch;
+};
+
+// Copy fp16 rows of every (b, h) from a strided tensor into a residual ring.
+struct CopyRowsParams {
+    const __half* src;    // element (b, h, t, c) at src[b*stride_b + h*stride_h + (src_t0 + t)*stride_t + c]
+    int64_t stride_b, stride_h, stride_t;
+    int32_t src_t0;
+    __half* dst;          // [b][h][cap_r][128]
+    int32_t dst_slot0;    // row t goes to slot (dst_slot0 + t) % cap_r
+    int32_t cap_r, n_tokens, n_kv_heads, batch;
+};
+
+// How the token axis [0, L) is cut into context splits (one workgroup each per (b, kv-head)).
+// Region A = tiles [0, tiles_a): K and V both quantised.  Region B = tiles [tiles_a, tiles_total):
+// at least one of K, V is fp16 there (5x the bytes per token), so its splits are shorter.
+struct SplitPlan {
+    int32_t tiles_a, tiles_total;
+    int32_t tiles_per_split_a, tiles_per_split_b;
+    int32_t n_splits_a, n_splits_b;
+    __host__ __device__ int32_t n_splits() const { return n_splits_a + n_splits_b; }
+};
+
+struct DecodeParams {
+    // cache
+    const uint32_t* k_codes; const __half* k_scale; const __half* k_zero;
+    const uint32_t* v_codes; const __half* v_scale; const __half* v_zero;
+    const __half* k_resid; const __half* v_resid;
+    int32_t n_kq, n_vq, k_r_start, n_kr, v_r_start, n_vr;
+    int32_t cap_tiles, cap_r;
+    // problem
+    const __half* q;        // [b][H_q][128]
+    float* out;             // [b][H_q][128]
+    float* part_ml;         // workspace: [b][H_q][n_splits][2]  (max, sum)
+    float* part_o;          // workspace: [b][H_q][n_splits][128]
+    float softmax_scale;
+    int32_t batch, n_q_heads, n_kv_heads, bits, length;
+    SplitPlan plan;
+};
+
+// launchers (each defined next to its kernels); they return hipGetLastError() after the launch
+hipError_t launch_quantize_keys(const QuantKeyParams& p, hipStream_t stream);
+hipError_t launch_quantize_values(const QuantValueParams& p, hipStream_t stream);
+hipError_t launch_copy_rows(const CopyRowsParams& p, hipStream_t stream);
+hipError_t launch_decode_valu(const DecodeParams& p, hipStream_t stream);
+hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream);
+hipError_t launch_merge(const DecodeParams& p, hipStream_t stream);
+
+}  // namespace kivi

@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2402_02750_amd import kivi
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(kivi.LIB_PATH):
+        from paper_2402_02750_amd.build import build_library
+        build_library(verbose=False)
+    return kivi.load_library()
+
+
+def test_exports_match_header(lib):
+    header = open(os.path.join(ROOT, "include", "kivi.h")).read()
+    declared = set(re.findall(r"^(?:int|const char\*)\s+(kivi_\w+)\s*\(", header, flags=re.M))
+    assert declared == set(kivi.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    assert kivi.status_string(0) == "KIVI_OK"
+    assert kivi.status_string(-1) == "KIVI_ERR_INVALID_ARG"
+    assert kivi.status_string(-2) == "KIVI_ERR_UNSUPPORTED"
+    assert kivi.status_string(-3) == "KIVI_ERR_WORKSPACE"
+    assert kivi.status_string(-4) == "KIVI_ERR_HIP"
+    assert kivi.status_string(-99) == "KIVI_ERR_UNKNOWN"
+
+
+def _layout(**kw):
+    base = dict(batch=2, n_q_heads=4, n_kv_heads=2, bits=2, residual=64, cap_q_tokens=256, cap_r_tokens=96)
+    base.update(kw)
+    return kivi.make_layout(**base)
+
+
+def test_cache_sizes_and_workspace(lib):
+    l = _layout()
+    s = kivi.kivi_cache_sizes(l)
+    units = 4
+    assert s.k_codes == s.v_codes == units * 8 * 1024
+    assert s.k_scale == s.k_zero == units * 8 * 128 * 2
+    assert s.v_scale == s.v_zero == units * 256 * 4 * 2
+    assert s.k_resid == s.v_resid == units * 96 * 128 * 2
+    l4 = _layout(bits=4)
+    assert kivi.kivi_cache_sizes(l4).k_codes == units * 8 * 2048
+    assert kivi.kivi_decode_workspace_bytes(l) >= 2 * 4 * 3 * 130 * 4
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(head_dim=64), kivi.KIVI_ERR_UNSUPPORTED),
+    (dict(bits=3), kivi.KIVI_ERR_UNSUPPORTED),
+    (dict(group=64), kivi.KIVI_ERR_UNSUPPORTED),
+    (dict(n_q_heads=3), kivi.KIVI_ERR_INVALID_ARG),
+    (dict(residual=48), kivi.KIVI_ERR_INVALID_ARG),           # R must be divisible by G
+    (dict(cap_q_tokens=100), kivi.KIVI_ERR_INVALID_ARG),
+    (dict(cap_r_tokens=64), kivi.KIVI_ERR_INVALID_ARG),       # needs R + G
+    (dict(batch=0), kivi.KIVI_ERR_INVALID_ARG),
+    (dict(decode_path=7), kivi.KIVI_ERR_INVALID_ARG),
+])
+def test_bad_layouts(lib, kw, status):
+    l = _layout(**kw)
+    sizes = kivi.kivi_cache_sizes_t()
+    assert lib.kivi_cache_sizes(ctypes.byref(l), ctypes.byref(sizes)) == status
+
+
+def _fake_cache(**kw):
+    """A cache whose pointers are aligned but never dereferenced (validation fails first)."""
+    c = kivi.kivi_cache_t()
+    for name in kivi.Cache._NAMES:
+        setattr(c, name, 0x1000)
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_entry_points_validate_before_launch(lib):
+    l = _layout()
+    good_ptr = ctypes.c_void_p(0x2000)
+    out = ctypes.c_void_p(0x3000)
+    # null / misaligned cache pointer
+    c = _fake_cache(k_codes=0)
+    assert lib.kivi_decode_attention(ctypes.byref(l), ctypes.byref(c), good_ptr, 0.1, out, good_ptr, 1 << 30, None) \
+        == kivi.KIVI_ERR_INVALID_ARG
+    c = _fake_cache(v_resid=0x1004)
+    assert lib.kivi_decode_attention(ctypes.byref(l), ctypes.byref(c), good_ptr, 0.1, out, good_ptr, 1 << 30, None) \
+        == kivi.KIVI_ERR_INVALID_ARG
+    # empty cache, inconsistent K/V lengths
+    c = _fake_cache()
+    assert lib.kivi_decode_attention(ctypes.byref(l), ctypes.byref(c), good_ptr, 0.1, out, good_ptr, 1 << 30, None) \
+        == kivi.KIVI_ERR_INVALID_ARG
+    c = _fake_cache(n_kq=64, n_kr=3, n_vq=64, n_vr=4)
+    assert lib.kivi_decode_attention(ctypes.byref(l), ctypes.byref(c), good_ptr, 0.1, out, good_ptr, 1 << 30, None) \
+        == kivi.KIVI_ERR_INVALID_ARG
+    # workspace missing / too small
+    c = _fake_cache(n_kq=64, n_kr=3, n_vq=64, n_vr=3)
+    assert lib.kivi_decode_attention(ctypes.byref(l), ctypes.byref(c), good_ptr, 0.1, out, None, 0, None) \
+        == kivi.KIVI_ERR_WORKSPACE
+    assert lib.kivi_decode_attention(ctypes.byref(l), ctypes.byref(c), good_ptr, 0.1, out, good_ptr, 64, None) \
+        == kivi.KIVI_ERR_WORKSPACE
+    # null q
+    assert lib.kivi_decode_attention(ctypes.byref(l), ctypes.byref(c), None, 0.1, out, good_ptr, 1 << 30, None) \
+        == kivi.KIVI_ERR_INVALID_ARG
+    # quantise: token count not a multiple of G, capacity exceeded, bad strides
+    c = _fake_cache()
+    f = lib.kivi_quantize_key_groups
+    assert f(ctypes.byref(l), good_ptr, 128 * 64 * 2, 128 * 64, 128, 33, ctypes.byref(c), None) == kivi.KIVI_ERR_INVALID_ARG
+    assert f(ctypes.byref(l), good_ptr, 128 * 64 * 2, 128 * 64, 128, 288, ctypes.byref(c), None) == kivi.KIVI_ERR_INVALID_ARG
+    assert f(ctypes.byref(l), good_ptr, 128 * 64 * 2, 128 * 64, 100, 32, ctypes.byref(c), None) == kivi.KIVI_ERR_INVALID_ARG
+    assert f(ctypes.byref(l), None, 128 * 64 * 2, 128 * 64, 128, 32, ctypes.byref(c), None) == kivi.KIVI_ERR_INVALID_ARG
+    assert c.n_kq == 0                                   # nothing advanced on error
+    g = lib.kivi_quantize_value_tokens
+    assert g(ctypes.byref(l), good_ptr, 128 * 64 * 2, 128 * 64, 128, 257, ctypes.byref(c), None) == kivi.KIVI_ERR_INVALID_ARG
+    # append into a full ring, unknown flush policy
+    c = _fake_cache(n_kr=96, n_vr=96)
+    assert lib.kivi_append_residual(ctypes.byref(l), ctypes.byref(c), good_ptr, good_ptr, None) == kivi.KIVI_ERR_INVALID_ARG
+    c = _fake_cache()
+    assert lib.kivi_flush_residual(ctypes.byref(l), ctypes.byref(c), 5, None, None, None) == kivi.KIVI_ERR_INVALID_ARG
+    # nothing to flush: OK without any launch
+    nk, nv = ctypes.c_int32(-1), ctypes.c_int32(-1)
+    c = _fake_cache(n_kr=70, n_vr=70)
+    assert lib.kivi_flush_residual(ctypes.byref(l), ctypes.byref(c), kivi.KIVI_FLUSH_WINDOW,
+                                   ctypes.byref(nk), ctypes.byref(nv), None) == kivi.KIVI_OK
+    assert (nk.value, nv.value) == (0, 0) and c.n_kr == 70

@@ -1,0 +1,148 @@
+"""GPU parity: the HIP path (through the C ABI) against the oracle on the same seeded inputs.
+
+Bar: packed codes, scales, zero-points and residual rows bit-exact; attention outputs within
+|gpu - ref| <= 2e-3 + 1e-2 |ref| element-wise.
+"""
+import numpy as np
+import pytest
+
+import gpu_harness as gh
+from oracle import kivi_oracle as ko
+from paper_2402_02750_amd import kivi, workloads
+from paper_2402_02750_amd.workloads import CONFIGS, scaled
+
+pytestmark = pytest.mark.gpu
+
+PATHS = [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA]
+PATH_IDS = ["valu", "mfma"]
+
+
+def _run_case(w, length, policy, path, heads=None):
+    torch = gh.require_gpu()
+    k = workloads.keys(w, length)
+    v = workloads.values(w, length)
+    q = workloads.queries(w)
+    layout, cache = gh.gpu_prefill(w, k, v, policy, path)
+    all_heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    heads = all_heads if heads is None else heads
+    oc = gh.oracle_cache_for_heads(w, k, v, heads, "window" if policy == kivi.KIVI_FLUSH_WINDOW else "alg1")
+    gh.compare_quantized_state(cache, oc, heads)
+    out = gh.gpu_attention(layout, cache, q, w.softmax_scale)
+    ref = gh.oracle_attention_for_heads(w, oc, q, heads)
+    return gh.check_close(gh.pick_heads(out, w, heads), ref, f"{w.name} L={length}")
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_config1_tiny(path):
+    """BASELINE config 1: batch 1, 4 heads, context 1024, 2-bit, R=32."""
+    w = CONFIGS["tiny"]
+    print(f"case tiny path={path}", flush=True)
+    _run_case(w, w.context, kivi.KIVI_FLUSH_WINDOW, path)
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("length", [1, 31, 32, 33, 127, 160, 161, 700, 2085])
+def test_lengths_and_ragged_tails(path, bits, length):
+    """Contexts shorter than R (nothing quantised), exactly at tile borders, and with ragged
+    residual tails; several splits at the long end."""
+    w = scaled(CONFIGS["llama7b"], name="small", batch=2, n_q_heads=3, n_kv_heads=3, bits=bits, seed=77 + bits)
+    print(f"case lengths path={path} bits={bits} L={length}", flush=True)
+    _run_case(w, length, kivi.KIVI_FLUSH_WINDOW, path)
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("rep", [2, 4, 8])
+def test_grouped_query(path, rep):
+    w = scaled(CONFIGS["mistral_gqa"], name="gqa_small", batch=2, n_q_heads=2 * rep, n_kv_heads=2, seed=500 + rep)
+    print(f"case gqa path={path} rep={rep}", flush=True)
+    _run_case(w, 1500, kivi.KIVI_FLUSH_WINDOW, path)
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("residual", [0, 32, 96])
+def test_residual_lengths(path, residual):
+    w = scaled(CONFIGS["llama7b"], name="resid", batch=1, n_q_heads=2, n_kv_heads=2, residual=residual, seed=900)
+    print(f"case residual path={path} R={residual}", flush=True)
+    _run_case(w, 640 + 17, kivi.KIVI_FLUSH_WINDOW, path)
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("length", [100, 200, 333, 1030])
+def test_alg1_split(path, bits, length):
+    """Algorithm 1's literal prefill: keys keep l % R tokens in fp16, values keep R, so the K and
+    V splits differ and the value part ends inside a tile."""
+    w = scaled(CONFIGS["llama7b"], name="alg1", batch=1, n_q_heads=2, n_kv_heads=2, bits=bits, seed=1200 + bits)
+    print(f"case alg1 path={path} bits={bits} L={length}", flush=True)
+    _run_case(w, length, kivi.KIVI_FLUSH_ALG1, path)
+
+
+def test_quantize_entry_points_append_in_pieces():
+    """kivi_quantize_key_groups / kivi_quantize_value_tokens called piecewise (strided source,
+    value pieces that end inside a tile) build the same cache as one call."""
+    torch = gh.require_gpu()
+    w = scaled(CONFIGS["llama7b"], name="pieces", batch=2, n_q_heads=2, n_kv_heads=2, seed=31)
+    n = 192
+    k = workloads.keys(w, n)
+    v = workloads.values(w, n)
+    layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, 256, 192)
+    cache = kivi.Cache(layout)
+    # source with padded token stride and swapped (h, b) memory order
+    kt = torch.zeros(w.n_kv_heads, w.batch, n, 136, dtype=torch.float16, device="cuda")
+    kt[..., :128] = torch.from_numpy(k).cuda().permute(1, 0, 2, 3)
+    kt = kt.permute(1, 0, 2, 3)[..., :128]
+    vt = torch.from_numpy(v).cuda()
+    for start, cnt in ((0, 64), (64, 32), (96, 96)):
+        kivi.kivi_quantize_key_groups(layout, kt[:, :, start:], cnt, cache)
+    for start, cnt in ((0, 5), (5, 27), (32, 1), (33, 70), (103, 89)):
+        kivi.kivi_quantize_value_tokens(layout, vt[:, :, start:], cnt, cache)
+    torch.cuda.synchronize()
+    assert (cache.c.n_kq, cache.c.n_vq) == (n, n)
+    ck, sk, zk = ko.quantize_key(k, w.bits, w.group)
+    cv, sv, zv = ko.quantize_value(v, w.bits, w.group)
+    assert np.array_equal(cache.view("k_codes")[:, :, :6].cpu().numpy().view(np.uint32), ko.pack_key_codes(ck, w.bits))
+    assert np.array_equal(cache.view("v_codes")[:, :, :6].cpu().numpy().view(np.uint32), ko.pack_value_codes(cv, w.bits))
+    assert np.array_equal(cache.view("k_scale")[:, :, :6].cpu().numpy().view(np.uint16), sk.view(np.uint16))
+    assert np.array_equal(cache.view("k_zero")[:, :, :6].cpu().numpy().view(np.uint16), zk.view(np.uint16))
+    assert np.array_equal(cache.view("v_scale")[:, :, :n].cpu().numpy().view(np.uint16), sv.view(np.uint16))
+    assert np.array_equal(cache.view("v_zero")[:, :, :n].cpu().numpy().view(np.uint16), zv.view(np.uint16))
+
+
+def test_quantizer_edge_values_bit_exact():
+    """Ties, constant groups, fp16 subnormal ranges and large magnitudes through the GPU quantiser."""
+    torch = gh.require_gpu()
+    rng = np.random.default_rng(5)
+    n = 64
+    k = np.zeros((1, 1, n, 128), np.float16)
+    k[0, 0, :, 0:16] = (rng.integers(-8, 9, size=(n, 16)) * 0.25)           # exact ties
+    k[0, 0, :, 16:32] = 0.75                                                 # constant groups
+    k[0, 0, :, 32:48] = (rng.integers(0, 6, size=(n, 16)) * 2.0 ** -24)      # subnormal ranges
+    k[0, 0, :, 48:64] = rng.standard_normal((n, 16)) * 3000                  # large magnitudes
+    k[0, 0, :, 64:] = rng.standard_normal((n, 64)) * 1e-3
+    v = np.ascontiguousarray(k[:, :, :, ::-1])
+    for bits in (2, 4):
+        layout = kivi.make_layout(1, 1, 1, bits, 32, 64, 96)
+        cache = kivi.Cache(layout)
+        kivi.kivi_quantize_key_groups(layout, torch.from_numpy(k).cuda(), n, cache)
+        kivi.kivi_quantize_value_tokens(layout, torch.from_numpy(v).cuda(), n, cache)
+        torch.cuda.synchronize()
+        ck, sk, zk = ko.quantize_key(k, bits, 32)
+        cv, sv, zv = ko.quantize_value(v, bits, 32)
+        assert np.array_equal(cache.view("k_scale").cpu().numpy().view(np.uint16), sk.view(np.uint16))
+        assert np.array_equal(cache.view("k_zero").cpu().numpy().view(np.uint16), zk.view(np.uint16))
+        assert np.array_equal(cache.view("k_codes").cpu().numpy().view(np.uint32), ko.pack_key_codes(ck, bits))
+        assert np.array_equal(cache.view("v_scale").cpu().numpy().view(np.uint16), sv.view(np.uint16))
+        assert np.array_equal(cache.view("v_zero").cpu().numpy().view(np.uint16), zv.view(np.uint16))
+        assert np.array_equal(cache.view("v_codes").cpu().numpy().view(np.uint32), ko.pack_value_codes(cv, bits))
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_run_twice_is_deterministic(path):
+    torch = gh.require_gpu()
+    w = scaled(CONFIGS["llama7b"], name="det", batch=2, n_q_heads=4, n_kv_heads=4, seed=3)
+    k, v, q = workloads.keys(w, 900), workloads.values(w, 900), workloads.queries(w)
+    layout, cache = gh.gpu_prefill(w, k, v, kivi.KIVI_FLUSH_WINDOW, path)
+    a = gh.gpu_attention(layout, cache, q, w.softmax_scale)
+    b = gh.gpu_attention(layout, cache, q, w.softmax_scale)
+    assert np.array_equal(a, b)

@@ -1,0 +1,48 @@
+"""GPU parity of the streaming path (append -> flush -> decode attention, BASELINE config 3
+shape at a size the oracle finishes quickly): cache state bit-exact after every flush, outputs
+within tolerance at every step."""
+import numpy as np
+import pytest
+
+import gpu_harness as gh
+from oracle import kivi_oracle as ko
+from paper_2402_02750_amd import kivi, workloads
+from paper_2402_02750_amd.workloads import CONFIGS, scaled
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("path", [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA], ids=["valu", "mfma"])
+@pytest.mark.parametrize("policy", [kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_FLUSH_ALG1], ids=["window", "alg1"])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_streaming_small(path, policy, bits):
+    torch = gh.require_gpu()
+    w = scaled(CONFIGS["stream"], name="stream_small", batch=2, n_q_heads=4, n_kv_heads=2, bits=bits,
+               residual=64, prompt=150, decode_steps=200, seed=4242 + bits)
+    total = w.prompt + w.decode_steps
+    k, v = workloads.keys(w, total), workloads.values(w, total)
+    print(f"case streaming path={path} policy={policy} bits={bits}", flush=True)
+    layout, cache = gh.gpu_prefill(w, k[:, :, :w.prompt], v[:, :, :w.prompt], policy, path,
+                                   extra_q_tokens=w.decode_steps)
+    oc = ko.StreamingCache(w.batch, w.n_kv_heads, 128, bits, w.group, w.residual,
+                           "window" if policy == kivi.KIVI_FLUSH_WINDOW else "alg1")
+    oc.prefill(k[:, :, :w.prompt], v[:, :, :w.prompt])
+    gh.compare_quantized_state(cache, oc)
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    worst = 0.0
+    for step in range(w.decode_steps):
+        t = w.prompt + step
+        kivi.kivi_append_residual(layout, cache, kt[:, :, t].contiguous(), vt[:, :, t].contiguous())
+        nk, nv = kivi.kivi_flush_residual(layout, cache, policy)
+        onk, onv = oc.append(k[:, :, t], v[:, :, t])
+        assert (nk, nv) == (onk, onv), f"step {step}"
+        if nk or nv or step % 37 == 0:
+            torch.cuda.synchronize()
+            gh.compare_quantized_state(cache, oc)
+        q = workloads.queries(w, step)
+        kivi.kivi_decode_attention(layout, cache, torch.from_numpy(q).cuda(), w.softmax_scale, out)
+        if step % 5 == 0 or nk or nv:
+            got = out.cpu().numpy()
+            worst = max(worst, gh.check_close(got, oc.attention(q, w.softmax_scale), f"step {step}"))
+    print(f"streaming worst abs err {worst:.3e}", flush=True)
