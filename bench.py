@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the KIVI decode-attention hot path on one MI355X.
+
+A step is one decode step at the workload's state: append the new token's key/value to the fp16
+residual window, run the flush check, and run decode attention over the mixed-precision cache
+(all through the C ABI).  Inputs are seeded synthetic tensors shaped like the paper's
+Llama-2 / Mistral layers and are resident in HBM before the timed region.  The cache is
+replicated `--copies` times and steps rotate over the copies so that every step streams its
+cache from HBM rather than from the 256 MB Infinity Cache ("cold"); the same-copy ("warm")
+figure is reported beside it.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+# HBM bytes per decode-attention launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# scaled by the factor a plain copy kernel of known size reads on the same counters; see the
+# summaries under profiles/.  None until measured for a workload/path.
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "llama13b_4bit", "mistral_gqa"])
+    ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--copies", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def cpu_baseline(w, k, v, q, seconds):
+    """Time the oracle's decode attention (as it stands) on a bounded sample of kv-heads."""
+    import numpy as np
+    from oracle import kivi_oracle as ko
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    n_q, n_r = w.split_single_step()
+    rep = w.q_per_kv
+    heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    done, t_total = 0, 0.0
+    for (b, h) in heads:
+        kk, vv = k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1]
+        kq = ko.quantize_key(kk[:, :, :n_q], w.bits, w.group)       # setup, not timed
+        vq = ko.quantize_value(vv[:, :, :n_q], w.bits, w.group)
+        qq = q[b:b + 1, h * rep:(h + 1) * rep]
+        t0 = time.perf_counter()
+        ko.decode_attention(qq, kq, kk[:, :, n_q:], vq, vv[:, :, n_q:], w.group, w.softmax_scale)
+        t_total += time.perf_counter() - t0
+        done += 1
+        if t_total >= seconds:
+            break
+    per_step = t_total / done * len(heads)
+    return {"value": w.batch / per_step, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"decode attention of {done} of {len(heads)} (batch, kv-head) units of the same workload, "
+                      f"{t_total:.1f} s, scaled to all units"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(how the path would shard is described in DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2402_02750_amd import kivi, workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    kivi.load_library()
+    torch.cuda.set_device(0)
+    w = workloads.CONFIGS[args.workload]
+    n_q, n_r = w.split_single_step()
+    L = w.context
+    path = {"auto": kivi.KIVI_DECODE_AUTO, "valu": kivi.KIVI_DECODE_VALU, "mfma": kivi.KIVI_DECODE_MFMA}[args.path]
+
+    k = workloads.keys(w, L)
+    v = workloads.values(w, L)
+    q = workloads.queries(w)
+    kt, vt, qt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(q).cuda()
+    cap_q = (n_q + 31) // 32 * 32 + 32
+    cap_r = w.residual + w.group + 32
+    layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, max(cap_q, 32), cap_r,
+                              decode_path=path)
+    stream = torch.cuda.current_stream()
+
+    # prefill (quantisation) -- timed separately, it is set-up for the decode step
+    caches = [kivi.Cache(layout) for _ in range(max(args.copies, 1))]
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    kivi.kivi_prefill(layout, kt, vt, L, caches[0])          # warm-up of the quantise kernels
+    caches[0].c.n_kq = caches[0].c.n_vq = caches[0].c.n_kr = caches[0].c.n_vr = 0
+    ev0.record(stream)
+    for c in caches:
+        kivi.kivi_prefill(layout, kt, vt, L, c)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    prefill_ms = ev0.elapsed_time(ev1) / len(caches)
+    assert (caches[0].c.n_kq, caches[0].c.n_kr) == (n_q, n_r)
+    k_new = kt[:, :, L - 1].contiguous()
+    v_new = vt[:, :, L - 1].contiguous()
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+
+    def step(c, ev_a=None, ev_b=None):
+        # the newest token is (re-)appended as the last residual token, then flush check, then attention
+        c.c.n_kr -= 1
+        c.c.n_vr -= 1
+        kivi.kivi_append_residual(layout, c, k_new, v_new, stream)
+        kivi.kivi_flush_residual(layout, c, kivi.KIVI_FLUSH_WINDOW, stream)
+        if ev_a is not None:
+            ev_a.record(stream)
+        kivi.kivi_decode_attention(layout, c, qt, w.softmax_scale, out, stream)
+        if ev_b is not None:
+            ev_b.record(stream)
+
+    def timed(n_steps, rotate):
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for i in range(n_steps):
+            step(caches[i % len(caches)] if rotate else caches[0], *pairs[i])
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        gpu_ms = ev0.elapsed_time(ev1)
+        attn_ms = sum(a.elapsed_time(b) for a, b in pairs) / n_steps
+        return gpu_ms / n_steps, attn_ms, wall_ms / n_steps
+
+    for i in range(args.warmup):
+        step(caches[i % len(caches)])
+    torch.cuda.synchronize()
+    cold_step_ms, cold_attn_ms, cold_wall_ms = timed(args.steps, rotate=True)
+    warm_step_ms, warm_attn_ms, _ = timed(args.steps, rotate=False)
+
+    bytes_ = w.algorithmic_bytes(n_q, n_r)
+    achieved = bytes_["all"] / (cold_attn_ms * 1e-3) / 1e9
+    achieved_packed = bytes_["packed"] / (cold_attn_ms * 1e-3) / 1e9
+    result = {
+        "metric": "decode-attn tokens/s over 2-bit KV; achieved HBM GB/s vs MI355X peak",
+        "value": w.batch / (cold_step_ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": cold_step_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": f"u{w.bits} codes, fp16 scale/zero/residual, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads, "
+                               f"head_dim 128, context {L} = {n_q} quantised ({w.bits}-bit, G=32) + {n_r} fp16 residual",
+                   "decode_path": args.path, "cache_copies_rotated": len(caches),
+                   "step": "append newest token + flush check + decode attention"},
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC.get((w.name, args.path)),
+            "kernel": "kivi_decode_attention (split kernel + merge), HIP events on the launch stream, cold cache copies",
+            "algorithmic_bytes_per_launch": bytes_["all"],
+            "achieved_packed_only": achieved_packed,
+            "frac_packed_only": achieved_packed / HBM_PEAK_GBS,
+            "launch_us": cold_attn_ms * 1e3,
+        },
+        "extra": {
+            "warm_ms_per_step": warm_step_ms, "warm_attn_us": warm_attn_ms * 1e3,
+            "warm_achieved_GBs": bytes_["all"] / (warm_attn_ms * 1e-3) / 1e9,
+            "host_wall_ms_per_step": cold_wall_ms,
+            "prefill_quantize_ms": prefill_ms,
+            "prefill_GBs": (2 * k.nbytes + bytes_["packed"] + bytes_["residual"]) / (prefill_ms * 1e-3) / 1e9,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, k, v, q, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
