@@ -181,8 +181,10 @@ int kivi_flush_residual(const kivi_layout_t* layout, kivi_cache_t* cache, int32_
  *                  j / (n_q_heads / n_kv_heads)
  *   softmax_scale  multiplies the logits before the softmax (1/sqrt(D) for the usual attention)
  *   out            device, fp32 [b][n_q_heads][128]
- *   workspace      device scratch of at least kivi_decode_workspace_bytes(layout) bytes; contents
- *                  need not be initialised and are undefined afterwards
+ *   workspace      device scratch of at least kivi_decode_workspace_bytes(layout) bytes.  It must be
+ *                  zero-filled once before its first use; every completed call leaves it ready
+ *                  for the next one (it starts with per-(batch, kv-head) counters that the
+ *                  kernel returns to zero).  Calls that share a workspace must not overlap.
  * Requires n_kq + n_kr == n_vq + n_vr >= 1.  The K and V splits may differ (Algorithm 1 splits
  * them differently).
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE, HIP.

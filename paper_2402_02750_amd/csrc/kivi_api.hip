@@ -51,13 +51,18 @@ int check_source(const void* x, int64_t sb, int64_t sh, int64_t st) {
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// The workspace starts with one finished-split counter per (batch, kv-head), padded to 256 bytes.
+size_t counter_bytes(const kivi_layout_t* l) {
+    return ((size_t)l->batch * l->n_kv_heads * sizeof(int32_t) + 255) / 256 * 256;
+}
+
 // Upper bound of the number of context splits for any cache state of this layout.
 int max_splits(const kivi_layout_t* l) {
     const int tiles = (l->cap_q_tokens + l->cap_r_tokens) / kTileTokens + 1;
     return tiles;   // every split covers at least one tile
 }
 
-SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c) {
+SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, int max_tiles) {
     SplitPlan s{};
     const int length = c->n_kq + c->n_kr;
     s.tiles_a = std::min(c->n_kq, c->n_vq) / kTileTokens;
@@ -68,15 +73,17 @@ SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c) {
     const int64_t units = (int64_t)l->batch * l->n_kv_heads;
     const int64_t target_wgs = 4096;
     const int rep = l->n_q_heads / l->n_kv_heads;
-    int tps = (int)std::min<int64_t>(kMaxSplitTiles, ((int64_t)s.tiles_a * units + target_wgs - 1) / target_wgs);
-    tps = std::max(tps, std::min(kMaxSplitTiles, 4 * rep));
-    s.tiles_per_split_a = std::max(1, std::min(tps, kMaxSplitTiles));
+    int tps = (int)std::min<int64_t>(max_tiles, ((int64_t)s.tiles_a * units + target_wgs - 1) / target_wgs);
+    tps = std::max(tps, std::min(max_tiles, 4 * rep));
+    s.tiles_per_split_a = std::max(1, std::min(tps, max_tiles));
     // fp16 rows cost 512 B per token against 96 B (2-bit) or 160 B (4-bit)
     const int packed_per_tile = kTileTokens * 2 * (kHeadDim * l->bits / 8 + 16);
     const int fp16_per_tile = kTileTokens * 2 * kHeadDim * 2;
-    s.tiles_per_split_b = std::max(1, std::min(8, s.tiles_per_split_a * packed_per_tile / fp16_per_tile));
+    const int tiles_b = s.tiles_total - s.tiles_a;
+    const int tps_b_max = std::max(1, std::min(8, s.tiles_per_split_a * packed_per_tile / fp16_per_tile));
+    s.n_splits_b = ceil_div(tiles_b, tps_b_max);
+    s.tiles_per_split_b = s.n_splits_b ? ceil_div(tiles_b, s.n_splits_b) : 1;     // even out the pieces
     s.n_splits_a = ceil_div(s.tiles_a, s.tiles_per_split_a);
-    s.n_splits_b = ceil_div(s.tiles_total - s.tiles_a, s.tiles_per_split_b);
     return s;
 }
 
@@ -141,7 +148,7 @@ int kivi_decode_workspace_bytes(const kivi_layout_t* l, size_t* bytes) {
     if (int st = check_layout(l)) return st;
     if (!bytes) return KIVI_ERR_INVALID_ARG;
     const size_t rows = (size_t)l->batch * l->n_q_heads * max_splits(l);
-    *bytes = rows * (kHeadDim + 2) * sizeof(float);
+    *bytes = counter_bytes(l) + rows * (kHeadDim + 2) * sizeof(float);
     return KIVI_OK;
 }
 
@@ -297,17 +304,19 @@ int kivi_decode_attention(const kivi_layout_t* l, const kivi_cache_t* c, const v
     p.softmax_scale = softmax_scale;
     p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
     p.length = length;
-    p.plan = plan_splits(l, c);
+    const int path = l->decode_path == KIVI_DECODE_AUTO ? KIVI_DECODE_MFMA : l->decode_path;
+    p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA ? kMfmaSplitTiles : kMaxSplitTiles);
     const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
-    p.part_o = static_cast<float*>(workspace);
+    p.counters = static_cast<int32_t*>(workspace);
+    p.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(l));
     p.part_ml = p.part_o + rows * kHeadDim;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    const int path = l->decode_path == KIVI_DECODE_AUTO ? KIVI_DECODE_VALU : l->decode_path;
     hipError_t e = path == KIVI_DECODE_MFMA ? launch_decode_mfma(p, hs) : launch_decode_valu(p, hs);
     if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
     if (int s = hip_status(e)) return s;
-    return hip_status(launch_merge(p, hs));
+    // the matrix-core kernel merges its splits itself; the vector-ALU family uses a second launch
+    return path == KIVI_DECODE_MFMA ? KIVI_OK : hip_status(launch_merge(p, hs));
 }
 
 }  // extern "C"

@@ -4,7 +4,7 @@
 // HBM speed a compute unit sees ~28 elements per clock while its vector ALUs retire 64 lane-ops
 // per clock.  Extract + convert + FMA + cross-lane reduction does not fit in ~2.3 lane-ops per
 // element.  Here the vector ALUs only *extract*: a code left in place inside an fp16 lane by one
-// AND is the exact subnormal/normal fp16 number code * 4^j * 2^-24, and the v_mfma 16x16x32 f16
+// AND is the exact subnormal fp16 number code * 4^j * 2^-24, and the v_mfma 16x16x32 f16
 // instruction multiplies, accumulates in fp32 and reduces over the contraction index.  The
 // position factor 4^j and the group's scale go into the small operand:
 //   keys  : a_t = sum_c [code_tc 4^j] [q_c s_c 4^-j]     + sum_c q_c z_c        (per tile of 32 tokens)
@@ -15,9 +15,14 @@
 // ALUs.
 //
 // A workgroup (4 wavefronts) owns one context split of one (batch, kv-head) and all query heads
-// reading it; each wavefront takes every 4th tile of the split as an independent sub-split with
-// its own softmax maximum (no barrier between logits and outputs); the four are merged in LDS and
-// one (m, l, o[128]) per query head goes to the workspace for merge_kernel.
+// reading it; each wavefront takes every 4th tile of the split (4 tile slots) as an independent
+// sub-split with its own softmax maximum, so there is no barrier between logits and outputs.  In
+// a split whose tiles are all quantised ("region A") a wavefront issues every global load of its
+// sub-split before it computes anything and runs branch-free (slots past the end of the split
+// re-read the last tile and are masked): the scan is latency-bound otherwise.  The four
+// sub-splits are merged in LDS, one (m, l, o[128]) per query head goes to the workspace, and the
+// last workgroup of a (batch, kv-head) to finish merges the splits (a counter in the workspace
+// tells which one that is), so one launch does the whole attention.
 #include "kivi_internal.h"
 
 #include <hip/hip_fp16.h>
@@ -28,12 +33,12 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-constexpr int kWaveTiles = kMaxSplitTiles / 4;          // 8 tiles per wavefront at most
-constexpr int kWaveTokens = kWaveTiles * kTileTokens;   // 256
+constexpr int kSlots = kMfmaSplitTiles / 4;             // tile slots per wavefront (4)
+constexpr int kWaveTokens = kSlots * kTileTokens;       // 128
 constexpr int kKRow = 136;   // halves per column of the key-side B staging (272 B: bank skew)
 constexpr int kVRow = 40;    // halves per column of the value-side B staging (80 B: bank skew)
-constexpr int kBStage = 4 * 16 * kVRow;                 // 2560 halves >= 16 * kKRow = 2176
 constexpr float kUnscale = 16777216.0f;                 // 2^24: codes enter as code * 2^-24
+constexpr float kDownscale = 1.0f / 16777216.0f;
 
 struct alignas(16) Half8 { __half2 v[4]; };
 
@@ -60,9 +65,41 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// value of lane+1 inside each pair of lanes (quad_perm [1,1,3,3])
-__device__ __forceinline__ float dpp_pair_next(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xF5, 0xF, 0xF, false));
+// data-parallel-primitive lane moves (all source lanes are valid for these patterns)
+template <int CTRL>
+__device__ __forceinline__ float dpp(float x) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i within 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15-i within 16
+constexpr int kDppRor4 = 0x124;        // rotate right by 4 within 16
+constexpr int kDppRor8 = 0x128;        // rotate right by 8 within 16
+
+__device__ __forceinline__ float readlane(float x, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+
+// all-lanes reductions over the 64 lanes (result uniform)
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp<kDppXor1>(v)); v = fmaxf(v, dpp<kDppXor2>(v));
+    v = fmaxf(v, dpp<kDppHalfMirror>(v)); v = fmaxf(v, dpp<kDppMirror>(v));
+    return fmaxf(fmaxf(readlane(v, 0), readlane(v, 16)), fmaxf(readlane(v, 32), readlane(v, 48)));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp<kDppXor1>(v); v += dpp<kDppXor2>(v);
+    v += dpp<kDppHalfMirror>(v); v += dpp<kDppMirror>(v);
+    return (readlane(v, 0) + readlane(v, 16)) + (readlane(v, 32) + readlane(v, 48));
+}
+
+// Device-scope (all compute dies) relaxed accesses: they bypass the per-die L2's write-back /
+// stale-line behaviour, which is what lets workgroups exchange results without cache flushes.
+__device__ __forceinline__ void device_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float device_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __device__ __forceinline__ float pow2_neg(int e) {   // 2^-e, 0 <= e < 64
@@ -106,80 +143,169 @@ __device__ __forceinline__ void split_hi_lo(float x, __half& hi, __half& lo) {
     lo = __float2half_rn(x - __half2float(hi));
 }
 
+// LDS of one wavefront.  `lr` holds, per matrix column (head, hi/lo), the raw matrix-core logits
+// of the wave's 128 token slots; after the softmax the hi column of a head holds its
+// probabilities and the lo column becomes the head's output staging row.
+template <int REP>
+struct WaveLds {
+    static constexpr int NC = 2 * REP;
+    static constexpr int kStageSlots = REP <= 2 ? 4 : (REP == 4 ? 2 : 1);   // tile slots staged at once
+    static constexpr int kKSlot = NC * kKRow;          // halves per staged key-side operand
+    static constexpr int kVSlot = 4 * NC * kVRow;      // halves per staged value-side operand
+    static constexpr int kBHalves = kStageSlots * (kKSlot > kVSlot ? kKSlot : kVSlot);
+    __align__(16) float lr[NC][kWaveTokens];
+    __align__(16) __half b[kBHalves];
+    __align__(16) float zt[NC][kSlots];
+};
+
+// Write the key-side small operand of one tile: columns (2hh, 2hh+1) = hi/lo of q_c s_c / posfactor.
+template <int REP>
+__device__ __forceinline__ void stage_key_operand(__half* bw, __half2 s2, const float (&qpf)[REP][2], int lane) {
+    const float s0 = __low2float(s2), s1 = __high2float(s2);
+#pragma unroll
+    for (int hh = 0; hh < REP; ++hh) {
+        __half h0, l0, h1, l1;
+        split_hi_lo(qpf[hh][0] * s0, h0, l0);
+        split_hi_lo(qpf[hh][1] * s1, h1, l1);
+        *reinterpret_cast<__half2*>(bw + (2 * hh) * kKRow + 2 * lane) = __halves2half2(h0, h1);
+        *reinterpret_cast<__half2*>(bw + (2 * hh + 1) * kKRow + 2 * lane) = __halves2half2(l0, l1);
+    }
+}
+
+// Raw logits of one quantised key tile: D = codes x operand; column n of D goes to lr[n][slot*32 + token].
+template <int BITS, int REP>
+__device__ __forceinline__ void key_tile_mfma(const uint32_t* w, const __half* bw, float (*lr)[kWaveTokens],
+                                              int slot, int lane) {
+    constexpr int NC = 2 * REP;
+    const int n = lane & 15, rq = lane >> 4, ncol = n & (NC - 1);
+    float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        const half8 bf = *reinterpret_cast<const half8*>(bw + ncol * kKRow + ks * 32 + rq * 8);
+        d0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_fragment<BITS>(w, ks, 0), bf, d0, 0, 0, 0);
+        d1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_fragment<BITS>(w, ks, 1), bf, d1, 0, 0, 0);
+    }
+    // d0[j]: token rq*4 + j, d1[j]: token 16 + rq*4 + j
+    if (n < NC) {
+        float* dst = &lr[n][slot * kTileTokens + rq * 4];
+        *reinterpret_cast<float4*>(dst) = make_float4(d0[0], d0[1], d0[2], d0[3]);
+        *reinterpret_cast<float4*>(dst + 16) = make_float4(d1[0], d1[1], d1[2], d1[3]);
+    }
+}
+
+// Write the value-side small operand of one tile (lane -> token lane/2, channel groups
+// (lane%2)*2 + {0,1}) and accumulate the z-term  sum_t p_t z_t,g.
+template <int BITS, int REP>
+__device__ __forceinline__ void stage_value_operand(__half* bw, __half2 s2, __half2 z2, int n_valid,
+                                                    const float (*lr)[kWaveTokens], int slot,
+                                                    float (&zacc)[REP][2], int lane) {
+    constexpr int NC = 2 * REP;
+    const int t = lane >> 1, cg0 = (lane & 1) * 2;
+    const bool valid = t < n_valid;
+    const float pf = inv_pos_factor<BITS>((t >> 1) & 3);
+    const float s0 = valid ? __low2float(s2) * pf : 0.f, s1 = valid ? __high2float(s2) * pf : 0.f;
+    const float z0 = valid ? __low2float(z2) : 0.f, z1 = valid ? __high2float(z2) : 0.f;
+#pragma unroll
+    for (int hh = 0; hh < REP; ++hh) {
+        const float pt = valid ? lr[2 * hh][slot * kTileTokens + t] : 0.f;
+        __half h0, l0, h1, l1;
+        split_hi_lo(pt * s0, h0, l0);
+        split_hi_lo(pt * s1, h1, l1);
+        bw[((cg0 + 0) * NC + 2 * hh) * kVRow + t] = h0;
+        bw[((cg0 + 0) * NC + 2 * hh + 1) * kVRow + t] = l0;
+        bw[((cg0 + 1) * NC + 2 * hh) * kVRow + t] = h1;
+        bw[((cg0 + 1) * NC + 2 * hh + 1) * kVRow + t] = l1;
+        zacc[hh][0] = fmaf(pt, z0, zacc[hh][0]);
+        zacc[hh][1] = fmaf(pt, z1, zacc[hh][1]);
+    }
+}
+
+template <int BITS, int REP>
+__device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half* bw, float4v (&acc)[8], int lane) {
+    constexpr int NC = 2 * REP;
+    const int n = lane & 15, rq = lane >> 4, ncol = n & (NC - 1);
+    half8 bf[4];
+#pragma unroll
+    for (int cg = 0; cg < 4; ++cg)
+        bf[cg] = *reinterpret_cast<const half8*>(bw + (cg * NC + ncol) * kVRow + rq * 8);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_fragment<BITS>(w, u >> 1, u & 1), bf[u >> 1],
+                                                        acc[u], 0, 0, 0);
+}
+
 template <int BITS, int REP>
 __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
+    using WL = WaveLds<REP>;
     constexpr int NC = 2 * REP;                       // live matrix columns: (head, hi/lo)
+    constexpr int SS = WL::kStageSlots;
     __shared__ __align__(16) float sm_q[REP][kHeadDim];               // scale * q
-    __shared__ __align__(16) __half sm_qf[16][kKRow];                 // its hi/lo columns (z-term operand)
-    __shared__ __align__(16) float sm_p[4][REP][kWaveTokens];         // logits -> probabilities -> staging
-    __shared__ __align__(16) __half sm_b[4][kBStage];                 // per-wave small-operand staging
-    __shared__ float sm_zt[4][REP][kWaveTiles];
+    __shared__ __align__(16) __half sm_qf[NC][kKRow];                 // its hi/lo columns (z-term operand)
+    __shared__ WL sm_w[4];
     __shared__ float sm_ml[4][REP][2];
+    __shared__ int sm_last;
 
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 15, rq = lane >> 4;          // matrix column / row-quad (= k-quad for operands)
+    const int ncol = n & (NC - 1);
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
     constexpr int kLaneWords = BITS * 2;
 
+    const bool region_a = split < p.plan.n_splits_a;
     int tile0, tile1;
-    if (split < p.plan.n_splits_a) {
+    if (region_a) {
         tile0 = split * p.plan.tiles_per_split_a;
         tile1 = min(tile0 + p.plan.tiles_per_split_a, p.plan.tiles_a);
     } else {
         tile0 = p.plan.tiles_a + (split - p.plan.n_splits_a) * p.plan.tiles_per_split_b;
         tile1 = min(tile0 + p.plan.tiles_per_split_b, p.plan.tiles_total);
     }
-    const int n_tiles = tile1 - tile0;
+    const int n_tiles = tile1 - tile0;                // 1 .. 16
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
     const int hq0 = h * REP;
+    // slot i of this wavefront is tile  tile0 + wave + 4*i  (valid while wave + 4*i < n_tiles)
+    const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
+    const int64_t ubase = unit * p.cap_tiles + tile0;
+
+    WL& wl = sm_w[wave];
+
+    // ---------------- region A: issue every load of the sub-split before anything else ---------
+    uint32_t kw[kSlots][kLaneWords], vw[kSlots][kLaneWords];
+    __half2 ks2[kSlots], vs2[kSlots], vz2[kSlots];
+    half8 zf[4];
+    if (region_a) {
+        const int64_t zt_tile = ubase + min(wave + 4 * min(n, kSlots - 1), n_tiles - 1);   // A row n = slot n
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            zf[ks] = *reinterpret_cast<const half8*>(p.k_zero + zt_tile * kHeadDim + ks * 32 + rq * 8);
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) {
+            const int64_t tile = ubase + min(wave + 4 * i, n_tiles - 1);
+            load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
+            ks2[i] = *reinterpret_cast<const __half2*>(p.k_scale + tile * kHeadDim + 2 * lane);
+        }
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) {
+            const int64_t tile = ubase + min(wave + 4 * i, n_tiles - 1);
+            load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
+            vs2[i] = *reinterpret_cast<const __half2*>(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
+            vz2[i] = *reinterpret_cast<const __half2*>(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+        }
+    }
 
     // ---------------- phase 0: query operands ----------------
-    for (int i = tid; i < 16 * kHeadDim; i += 256) {
-        const int col = i / kHeadDim, c = i % kHeadDim;
-        __half v = __float2half_rn(0.f);
-        if (col < NC) {
-            const int hh = col >> 1;
-            const float x = p.softmax_scale *
-                            __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]);
-            __half hi, lo;
-            split_hi_lo(x, hi, lo);
-            v = (col & 1) ? lo : hi;
-            if (!(col & 1)) sm_q[hh][c] = x;
-        }
-        sm_qf[col][c] = v;
+    for (int i = tid; i < REP * kHeadDim; i += 256) {
+        const int hh = i / kHeadDim, c = i % kHeadDim;
+        const float x = p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]);
+        __half hi, lo;
+        split_hi_lo(x, hi, lo);
+        sm_q[hh][c] = x;
+        sm_qf[2 * hh][c] = hi;
+        sm_qf[2 * hh + 1][c] = lo;
     }
+    if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
     __syncthreads();
-
-    // tiles of this wavefront: ti = wave + 4*i
-    const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
-    // how many of them are quantised key tiles (they come first in token order)
-    int cnt_kq = 0;
-    for (int i = 0; i < cnt; ++i) cnt_kq += ((tile0 + wave + 4 * i) * kTileTokens < p.n_kq) ? 1 : 0;
-
-    __half* bw = sm_b[wave];
-    const int ncol = n & (NC - 1);
-
-    // ---------------- key z-terms of all quantised tiles of the wave: one 16x16x128 product ----
-    if (cnt_kq > 0) {
-        const int ti = wave + 4 * min(n, cnt_kq - 1);           // row n of A = n-th tile of the wave
-        const __half* zrow = p.k_zero + (unit * p.cap_tiles + tile0 + ti) * kHeadDim;
-        float4v d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const half8 a = *reinterpret_cast<const half8*>(zrow + ks * 32 + rq * 8);
-            const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[n][ks * 32 + rq * 8]);
-            d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bq, d, 0, 0, 0);
-        }
-        // d[i]: tile index rq*4 + i of the wave, column n; hi + lo columns
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float v = d[i] + dpp_pair_next(d[i]);
-            const int idx = rq * 4 + i;
-            if (!(n & 1) && n < NC && idx < kWaveTiles) sm_zt[wave][n >> 1][idx] = v;
-        }
-        wave_lds_sync();
-    }
 
     // per-lane key-side query factors: channels 2*lane, 2*lane+1 times 1/position factor
     float qpf[REP][2];
@@ -192,114 +318,30 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
         }
     }
 
-    // ---------------- phase 1: logits of the wave's tiles ----------------
-    for (int i = 0; i < cnt; ++i) {
-        const int tile = tile0 + wave + 4 * i;
-        const int tt = tile * kTileTokens;
-        if (tt < p.n_kq) {
-            uint32_t w[kLaneWords];
-            load_tile_words<BITS>(p.k_codes + (unit * p.cap_tiles + tile) * kWords, lane, w);
-            const __half2 s2 = *reinterpret_cast<const __half2*>(
-                p.k_scale + (unit * p.cap_tiles + tile) * kHeadDim + 2 * lane);
-            const float s0 = __low2float(s2), s1 = __high2float(s2);
+    // how many of the wave's tiles are quantised key tiles (they come first in token order)
+    int cnt_kq = cnt;
+    if (!region_a) {
+        cnt_kq = 0;
+        for (int i = 0; i < cnt; ++i) cnt_kq += ((tile0 + wave + 4 * i) * kTileTokens < p.n_kq) ? 1 : 0;
+        if (cnt_kq > 0) {
+            const __half* zrow = p.k_zero + (ubase + wave + 4 * min(n, cnt_kq - 1)) * kHeadDim;
 #pragma unroll
-            for (int hh = 0; hh < REP; ++hh) {
-                __half h0, l0, h1, l1;
-                split_hi_lo(qpf[hh][0] * s0, h0, l0);
-                split_hi_lo(qpf[hh][1] * s1, h1, l1);
-                *reinterpret_cast<__half2*>(bw + (2 * hh) * kKRow + 2 * lane) = __halves2half2(h0, h1);
-                *reinterpret_cast<__half2*>(bw + (2 * hh + 1) * kKRow + 2 * lane) = __halves2half2(l0, l1);
-            }
-            wave_lds_sync();
-            half8 bf[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                bf[ks] = *reinterpret_cast<const half8*>(bw + ncol * kKRow + ks * 32 + rq * 8);
-            wave_lds_sync();
-            float4v d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                d0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_fragment<BITS>(w, ks, 0), bf[ks], d0, 0, 0, 0);
-                d1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_fragment<BITS>(w, ks, 1), bf[ks], d1, 0, 0, 0);
-            }
-            // d0[j]: token rq*4 + j, d1[j]: token 16 + rq*4 + j; column n
-            float v0[4], v1[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                v0[j] = d0[j] + dpp_pair_next(d0[j]);
-                v1[j] = d1[j] + dpp_pair_next(d1[j]);
-            }
-            if (!(n & 1) && n < NC) {
-                const int hh = n >> 1;
-                const float zt = sm_zt[wave][hh][i];
-                float* dst = &sm_p[wave][hh][i * kTileTokens + rq * 4];
-                *reinterpret_cast<float4*>(dst) = make_float4(
-                    fmaf(v0[0], kUnscale, zt), fmaf(v0[1], kUnscale, zt),
-                    fmaf(v0[2], kUnscale, zt), fmaf(v0[3], kUnscale, zt));
-                *reinterpret_cast<float4*>(dst + 16) = make_float4(
-                    fmaf(v1[0], kUnscale, zt), fmaf(v1[1], kUnscale, zt),
-                    fmaf(v1[2], kUnscale, zt), fmaf(v1[3], kUnscale, zt));
-            }
-        } else {
-            // fp16 residual keys on the vector ALUs: lane (seg, row): 4 rows per step, 8 channels per lane
-            const int seg = lane & 15, row = lane >> 4;
-            float qv[REP][8];
-#pragma unroll
-            for (int hh = 0; hh < REP; ++hh)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) qv[hh][e] = sm_q[hh][seg * 8 + e];
-#pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int t = tt + it * 4 + row;
-                const bool valid = t < p.length;
-                float k[8];
-                if (valid) {
-                    const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
-                    unpack8(*reinterpret_cast<const Half8*>(
-                                p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8), k);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) k[e] = 0.f;
-                }
-#pragma unroll
-                for (int hh = 0; hh < REP; ++hh) {
-                    float a = 0.f;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) a = fmaf(qv[hh][e], k[e], a);
-                    a += __shfl_xor(a, 1); a += __shfl_xor(a, 2);
-                    a += __shfl_xor(a, 4); a += __shfl_xor(a, 8);
-                    if (seg == 0) sm_p[wave][hh][i * kTileTokens + it * 4 + row] = valid ? a : -INFINITY;
-                }
-            }
+            for (int ks = 0; ks < 4; ++ks) zf[ks] = *reinterpret_cast<const half8*>(zrow + ks * 32 + rq * 8);
         }
     }
-    wave_lds_sync();
 
-    // ---------------- phase 2: softmax statistics of the wave's sub-split ----------------
-    float m_w[REP], l_w[REP];
+    // ---------------- key z-terms of the wave's quantised tiles: one 16x16x128 product ----------
+    if (cnt_kq > 0) {
+        float4v d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int hh = 0; hh < REP; ++hh) {
-        m_w[hh] = -INFINITY;
-        l_w[hh] = 0.f;
-        if (cnt > 0) {
-            float4 a = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-            const bool live = lane * 4 < cnt * kTileTokens;
-            if (live) a = *reinterpret_cast<const float4*>(&sm_p[wave][hh][lane * 4]);
-            float mx = fmaxf(fmaxf(a.x, a.y), fmaxf(a.z, a.w));
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-            a.x = __expf(a.x - mx); a.y = __expf(a.y - mx); a.z = __expf(a.z - mx); a.w = __expf(a.w - mx);
-            if (live) *reinterpret_cast<float4*>(&sm_p[wave][hh][lane * 4]) = a;
-            float sum = live ? (a.x + a.y) + (a.z + a.w) : 0.f;
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-            m_w[hh] = mx;
-            l_w[hh] = sum;
+        for (int ks = 0; ks < 4; ++ks) {
+            const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[ncol][ks * 32 + rq * 8]);
+            d = __builtin_amdgcn_mfma_f32_16x16x32_f16(zf[ks], bq, d, 0, 0, 0);
         }
+        // d[j]: slot rq*4 + j (rows 0..3 are the wave's slots), column n
+        if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
     }
-    wave_lds_sync();
 
-    // ---------------- phase 3: outputs of the wave's tiles ----------------
     float4v acc[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
@@ -310,63 +352,69 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) racc[hh][e] = 0.f;
     }
-    for (int i = 0; i < cnt; ++i) {
-        const int tile = tile0 + wave + 4 * i;
-        const int tt = tile * kTileTokens;
-        const int n_vq_here = min(max(p.n_vq - tt, 0), kTileTokens);
-        if (n_vq_here > 0) {
-            uint32_t w[kLaneWords];
-            load_tile_words<BITS>(p.v_codes + (unit * p.cap_tiles + tile) * kWords, lane, w);
-            // lane -> token t = lane/2, channel groups (lane%2)*2 + {0,1}
-            const int t = lane >> 1, cg0 = (lane & 1) * 2;
-            const bool valid = t < n_vq_here;
-            const int64_t so = ((unit * p.cap_tiles + tile) * kTileTokens) * 4 + 2 * lane;
-            const __half2 s2 = *reinterpret_cast<const __half2*>(p.v_scale + so);
-            const __half2 z2 = *reinterpret_cast<const __half2*>(p.v_zero + so);
-            const float pf = inv_pos_factor<BITS>((t >> 1) & 3);
-            const float s0 = valid ? __low2float(s2) * pf : 0.f, s1 = valid ? __high2float(s2) * pf : 0.f;
-            const float z0 = valid ? __low2float(z2) : 0.f, z1 = valid ? __high2float(z2) : 0.f;
+
+    // ---------------- phase 1: raw logits of the wave's tiles ----------------
+    if (region_a) {
 #pragma unroll
-            for (int hh = 0; hh < REP; ++hh) {
-                const float pt = valid ? sm_p[wave][hh][i * kTileTokens + t] : 0.f;
-                __half h0, l0, h1, l1;
-                split_hi_lo(pt * s0, h0, l0);
-                split_hi_lo(pt * s1, h1, l1);
-                bw[((cg0 + 0) * 16 + 2 * hh) * kVRow + t] = h0;
-                bw[((cg0 + 0) * 16 + 2 * hh + 1) * kVRow + t] = l0;
-                bw[((cg0 + 1) * 16 + 2 * hh) * kVRow + t] = h1;
-                bw[((cg0 + 1) * 16 + 2 * hh + 1) * kVRow + t] = l1;
-                zacc[hh][0] = fmaf(pt, z0, zacc[hh][0]);
-                zacc[hh][1] = fmaf(pt, z1, zacc[hh][1]);
-            }
-            wave_lds_sync();
-            half8 bf[4];
+        for (int c0 = 0; c0 < kSlots; c0 += SS) {
 #pragma unroll
-            for (int cg = 0; cg < 4; ++cg)
-                bf[cg] = *reinterpret_cast<const half8*>(bw + (cg * 16 + ncol) * kVRow + rq * 8);
+            for (int s = 0; s < SS; ++s) stage_key_operand<REP>(wl.b + s * WL::kKSlot, ks2[c0 + s], qpf, lane);
             wave_lds_sync();
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_fragment<BITS>(w, u >> 1, u & 1),
-                                                                bf[u >> 1], acc[u], 0, 0, 0);
+            for (int s = 0; s < SS; ++s)
+                key_tile_mfma<BITS, REP>(kw[c0 + s], wl.b + s * WL::kKSlot, wl.lr, c0 + s, lane);
+            wave_lds_sync();
         }
-        if (n_vq_here < kTileTokens) {
-            // fp16 residual values on the vector ALUs: lane (seg, row)
-            const int seg = lane & 15, row = lane >> 4;
+    } else {
+        for (int i = 0; i < cnt; ++i) {
+            const int tile = tile0 + wave + 4 * i;
+            const int tt = tile * kTileTokens;
+            if (tt < p.n_kq) {
+                uint32_t w[kLaneWords];
+                load_tile_words<BITS>(p.k_codes + (ubase + wave + 4 * i) * kWords, lane, w);
+                const __half2 s2 = *reinterpret_cast<const __half2*>(
+                    p.k_scale + (ubase + wave + 4 * i) * kHeadDim + 2 * lane);
+                stage_key_operand<REP>(wl.b, s2, qpf, lane);
+                wave_lds_sync();
+                key_tile_mfma<BITS, REP>(w, wl.b, wl.lr, i, lane);
+                wave_lds_sync();
+            } else {
+                // fp16 residual keys on the vector ALUs: lane (seg, row): 4 rows per step, 8 channels.
+                // The finished logit a is stored as a * 2^-24 in the head's hi column (lo column and
+                // z-term 0), which the softmax below turns back into a exactly.
+                const int seg = lane & 15, row = lane >> 4;
+                float qv[REP][8];
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int tl = it * 4 + row;
-                const int t = tt + tl;
-                if (tl >= n_vq_here && t < p.length) {
-                    const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
-                    float v[8];
-                    unpack8(*reinterpret_cast<const Half8*>(
-                                p.v_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8), v);
+                for (int hh = 0; hh < REP; ++hh)
 #pragma unroll
-                    for (int hh = 0; hh < REP; ++hh) {
-                        const float pt = sm_p[wave][hh][i * kTileTokens + tl];
+                    for (int e = 0; e < 8; ++e) qv[hh][e] = sm_q[hh][seg * 8 + e];
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, v[e], racc[hh][e]);
+                for (int half = 0; half < 2; ++half) {
+                    Half8 kr[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {    // rows past the end re-read the last row
+                        const int t = min(tt + (half * 4 + j) * 4 + row, p.length - 1);
+                        const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
+                        kr[j] = *reinterpret_cast<const Half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int tl = (half * 4 + j) * 4 + row;
+                        const bool valid = tt + tl < p.length;
+                        float k[8];
+                        unpack8(kr[j], k);
+#pragma unroll
+                        for (int hh = 0; hh < REP; ++hh) {
+                            float a = 0.f;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) a = fmaf(qv[hh][e], k[e], a);
+                            a += dpp<kDppXor1>(a); a += dpp<kDppXor2>(a);
+                            a += dpp<kDppHalfMirror>(a); a += dpp<kDppMirror>(a);
+                            if (seg == 0) {
+                                wl.lr[2 * hh][i * kTileTokens + tl] = valid ? a * kDownscale : -INFINITY;
+                                wl.lr[2 * hh + 1][i * kTileTokens + tl] = 0.f;
+                            }
+                        }
                     }
                 }
             }
@@ -374,60 +422,144 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
     }
     wave_lds_sync();
 
-    // ---------------- wave results -> LDS (the probability area becomes the staging area) -------
-    // stage[hh][0][c]: matrix-core part (+ z-terms), stage[hh][1][c]: vector-ALU residual part
+    // ---------------- phase 2: softmax of the wave's sub-split (2 token slots per lane) ---------
+    float m_w[REP], l_w[REP];
     {
-        // z-term sums: lanes of equal parity hold the same channel-group pair
+        const int slot = lane >> 4;
+        const bool live = slot < cnt;
 #pragma unroll
-        for (int hh = 0; hh < REP; ++hh)
+        for (int hh = 0; hh < REP; ++hh) {
+            const float2 hi = *reinterpret_cast<const float2*>(&wl.lr[2 * hh][2 * lane]);
+            const float2 lo = *reinterpret_cast<const float2*>(&wl.lr[2 * hh + 1][2 * lane]);
+            const float zt = wl.zt[2 * hh][slot] + wl.zt[2 * hh + 1][slot];
+            const float a0 = live ? fmaf(hi.x + lo.x, kUnscale, zt) : -INFINITY;
+            const float a1 = live ? fmaf(hi.y + lo.y, kUnscale, zt) : -INFINITY;
+            const float mx = wave_max(fmaxf(a0, a1));
+            const float ms = mx == -INFINITY ? 0.f : mx;
+            const float p0 = __expf(a0 - ms), p1 = __expf(a1 - ms);
+            *reinterpret_cast<float2*>(&wl.lr[2 * hh][2 * lane]) = make_float2(p0, p1);
+            m_w[hh] = mx;
+            l_w[hh] = wave_sum(p0 + p1);
+        }
+    }
+    wave_lds_sync();
+
+    // ---------------- phase 3: outputs of the wave's tiles ----------------
+    if (region_a) {
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                float zz = zacc[hh][k];
-                zz += __shfl_xor(zz, 2); zz += __shfl_xor(zz, 4); zz += __shfl_xor(zz, 8);
-                zz += __shfl_xor(zz, 16); zz += __shfl_xor(zz, 32);
-                zacc[hh][k] = zz;
+        for (int c0 = 0; c0 < kSlots; c0 += SS) {
+#pragma unroll
+            for (int s = 0; s < SS; ++s)
+                stage_value_operand<BITS, REP>(wl.b + s * WL::kVSlot, vs2[c0 + s], vz2[c0 + s],
+                                               c0 + s < cnt ? kTileTokens : 0, wl.lr, c0 + s, zacc, lane);
+            wave_lds_sync();
+#pragma unroll
+            for (int s = 0; s < SS; ++s) value_tile_mfma<BITS, REP>(vw[c0 + s], wl.b + s * WL::kVSlot, acc, lane);
+            wave_lds_sync();
+        }
+    } else {
+        for (int i = 0; i < cnt; ++i) {
+            const int tile = tile0 + wave + 4 * i;
+            const int tt = tile * kTileTokens;
+            const int n_vq_here = min(max(p.n_vq - tt, 0), kTileTokens);
+            if (n_vq_here > 0) {
+                uint32_t w[kLaneWords];
+                load_tile_words<BITS>(p.v_codes + (ubase + wave + 4 * i) * kWords, lane, w);
+                const int64_t so = (ubase + wave + 4 * i) * kTileTokens * 4 + 2 * lane;
+                const __half2 s2 = *reinterpret_cast<const __half2*>(p.v_scale + so);
+                const __half2 z2 = *reinterpret_cast<const __half2*>(p.v_zero + so);
+                stage_value_operand<BITS, REP>(wl.b, s2, z2, n_vq_here, wl.lr, i, zacc, lane);
+                wave_lds_sync();
+                value_tile_mfma<BITS, REP>(w, wl.b, acc, lane);
+                wave_lds_sync();
             }
-        // every lane needs all four channel-group sums of "its" head (n >> 1)
+            if (n_vq_here < kTileTokens && p.n_vr > 0) {
+                // fp16 residual values on the vector ALUs: lane (seg, row)
+                const int seg = lane & 15, row = lane >> 4;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    Half8 vr[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {    // clamped rows are loaded but not used
+                        const int t = min(max(tt + (half * 4 + j) * 4 + row, p.n_vq), p.length - 1);
+                        const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
+                        vr[j] = *reinterpret_cast<const Half8*>(p.v_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int tl = (half * 4 + j) * 4 + row;
+                        const bool use = tl >= n_vq_here && tt + tl < p.length;
+                        float v[8];
+                        unpack8(vr[j], v);
+#pragma unroll
+                        for (int hh = 0; hh < REP; ++hh) {
+                            const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, v[e], racc[hh][e]);
+                        }
+                    }
+                }
+            }
+        }
+    }
+    wave_lds_sync();
+
+    // ---------------- wave results -> LDS: the lo column of a head becomes its output row -------
+    {
+        // z-term sums over tokens: lanes of equal parity hold the same channel-group pair, so
+        // reduce with parity-preserving moves (xor 2, rotate by 4 and 8 inside a row, then rows)
         float zs[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int hh = 0; hh < REP; ++hh) {
-            const float o0 = __shfl_xor(zacc[hh][0], 1), o1 = __shfl_xor(zacc[hh][1], 1);
-            const bool odd = lane & 1;
-            const float g0 = odd ? o0 : zacc[hh][0], g1 = odd ? o1 : zacc[hh][1];
-            const float g2 = odd ? zacc[hh][0] : o0, g3 = odd ? zacc[hh][1] : o1;
-            if ((n >> 1) == hh) { zs[0] = g0; zs[1] = g1; zs[2] = g2; zs[3] = g3; }
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                float zz = zacc[hh][k];
+                zz += dpp<kDppXor2>(zz); zz += dpp<kDppRor4>(zz); zz += dpp<kDppRor8>(zz);
+                zz += __shfl_xor(zz, 16); zz += __shfl_xor(zz, 32);
+                const float other = dpp<kDppXor1>(zz);          // the other parity's pair of groups
+                const bool odd = lane & 1;
+                if ((n >> 1) == hh) { zs[k] = odd ? other : zz; zs[2 + k] = odd ? zz : other; }
+            }
         }
-        float* stage = &sm_p[wave][0][0];       // REP * 256 floats = REP * (2 * 128)
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             float v[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = acc[u][j] + dpp_pair_next(acc[u][j]);
+            for (int j = 0; j < 4; ++j) v[j] = acc[u][j] + dpp<kDppXor1>(acc[u][j]);   // hi + lo column
             if (!(n & 1) && n < NC) {
                 const float z = zs[u >> 1];
-                *reinterpret_cast<float4*>(stage + (n >> 1) * 256 + u * 16 + rq * 4) = make_float4(
+                *reinterpret_cast<float4*>(&wl.lr[n + 1][u * 16 + rq * 4]) = make_float4(
                     fmaf(v[0], kUnscale, z), fmaf(v[1], kUnscale, z), fmaf(v[2], kUnscale, z), fmaf(v[3], kUnscale, z));
             }
         }
+        if (!region_a) {
+            wave_lds_sync();
 #pragma unroll
-        for (int hh = 0; hh < REP; ++hh) {
+            for (int hh = 0; hh < REP; ++hh) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float rr = racc[hh][e];
-                rr += __shfl_xor(rr, 16); rr += __shfl_xor(rr, 32);
-                racc[hh][e] = rr;
+                for (int e = 0; e < 8; ++e) {
+                    float rr = racc[hh][e];
+                    rr += __shfl_xor(rr, 16); rr += __shfl_xor(rr, 32);
+                    racc[hh][e] = rr;
+                }
+                if (lane < 16) {
+                    float* dst = &wl.lr[2 * hh + 1][lane * 8];
+                    float4 a = *reinterpret_cast<float4*>(dst), c = *reinterpret_cast<float4*>(dst + 4);
+                    a.x += racc[hh][0]; a.y += racc[hh][1]; a.z += racc[hh][2]; a.w += racc[hh][3];
+                    c.x += racc[hh][4]; c.y += racc[hh][5]; c.z += racc[hh][6]; c.w += racc[hh][7];
+                    *reinterpret_cast<float4*>(dst) = a;
+                    *reinterpret_cast<float4*>(dst + 4) = c;
+                }
             }
-            if (lane < 16) {
-                float* dst = stage + hh * 256 + 128 + lane * 8;
-                *reinterpret_cast<float4*>(dst) = make_float4(racc[hh][0], racc[hh][1], racc[hh][2], racc[hh][3]);
-                *reinterpret_cast<float4*>(dst + 4) = make_float4(racc[hh][4], racc[hh][5], racc[hh][6], racc[hh][7]);
-            }
-            if (lane == 0) { sm_ml[wave][hh][0] = m_w[hh]; sm_ml[wave][hh][1] = l_w[hh]; }
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int hh = 0; hh < REP; ++hh) { sm_ml[wave][hh][0] = m_w[hh]; sm_ml[wave][hh][1] = l_w[hh]; }
         }
     }
     __syncthreads();
 
-    // ---------------- merge the four sub-splits, write the split's partial result ----------------
+    // ---------------- merge the four sub-splits ----------------
     const int n_splits = p.plan.n_splits();
     for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
         const int hh = idx / kHeadDim, c = idx % kHeadDim;
@@ -440,23 +572,56 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
             const float mw = sm_ml[wv][hh][0];
             if (mw > -INFINITY) {
                 const float wgt = __expf(mw - m);
-                const float* st = &sm_p[wv][0][0] + hh * 256;
                 l = fmaf(sm_ml[wv][hh][1], wgt, l);
-                o = fmaf(st[c] + st[128 + c], wgt, o);
+                o = fmaf(sm_w[wv].lr[2 * hh + 1][c], wgt, o);
             }
         }
-        const int64_t row = ((int64_t)b * p.n_q_heads + hq0 + hh) * n_splits + split;
-        p.part_o[row * kHeadDim + c] = o;
-        if (c == 0) {
-            p.part_ml[row * 2 + 0] = m;
-            p.part_ml[row * 2 + 1] = l;
+        const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
+        if (n_splits == 1) {
+            p.out[row * kHeadDim + c] = o / l;
+        } else {
+            // device-scope stores: they go through to memory, no cache flush is needed to publish them
+            device_store(p.part_o + (row * n_splits + split) * kHeadDim + c, o);
+            if (c == 0) {
+                device_store(p.part_ml + (row * n_splits + split) * 2 + 0, m);
+                device_store(p.part_ml + (row * n_splits + split) * 2 + 1, l);
+            }
         }
     }
+    if (n_splits == 1) return;
+
+    // ---------------- the last workgroup of this (batch, kv-head) merges the splits ------------
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // wait until the stores above are acknowledged
+    __syncthreads();
+    if (tid == 0) {
+        const int done = __hip_atomic_fetch_add(p.counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sm_last = (done == n_splits - 1);
+    }
+    __syncthreads();
+    if (!sm_last) return;
+    for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
+        const int hh = idx / kHeadDim, c = idx % kHeadDim;
+        const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
+        const float* ml = p.part_ml + row * n_splits * 2;
+        const float* po = p.part_o + row * n_splits * kHeadDim;
+        float m = -INFINITY;
+        for (int i = 0; i < n_splits; ++i) m = fmaxf(m, device_load(ml + 2 * i));
+        float l = 0.f, o = 0.f;
+        for (int i = 0; i < n_splits; ++i) {
+            const float wgt = __expf(device_load(ml + 2 * i) - m);
+            l = fmaf(device_load(ml + 2 * i + 1), wgt, l);
+            o = fmaf(device_load(po + (int64_t)i * kHeadDim + c), wgt, o);
+        }
+        p.out[row * kHeadDim + c] = o / l;
+    }
+    if (tid == 0) __hip_atomic_store(p.counters + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int BITS>
 hipError_t launch_bits(const DecodeParams& p, hipStream_t stream) {
     const int rep = p.n_q_heads / p.n_kv_heads;
+    if (p.plan.tiles_per_split_a > kMfmaSplitTiles || p.plan.tiles_per_split_b > kMfmaSplitTiles)
+        return hipErrorInvalidValue;
     dim3 grid(p.plan.n_splits(), p.n_kv_heads, p.batch), block(256);
     switch (rep) {
         case 1: decode_mfma_kernel<BITS, 1><<<grid, block, 0, stream>>>(p); break;

@@ -13,6 +13,7 @@ namespace kivi {
 constexpr int kHeadDim = 128;
 constexpr int kTileTokens = 32;        // tokens per code tile == supported group size G
 constexpr int kMaxSplitTiles = 32;     // a context split covers at most 32 tiles (1024 tokens)
+constexpr int kMfmaSplitTiles = 16;    // ... at most 16 tiles in the matrix-core family (4 per wavefront)
 constexpr int kMaxRep = 8;             // query heads per kv-head handled by one workgroup pass
 
 // Source of fp16 rows for the quantise kernels: either a strided tensor or a ring buffer.
@@ -75,6 +76,7 @@ struct DecodeParams {
     // problem
     const __half* q;        // [b][H_q][128]
     float* out;             // [b][H_q][128]
+    int32_t* counters;      // workspace: [b][H_kv] finished-split counters (zero between calls)
     float* part_ml;         // workspace: [b][H_q][n_splits][2]  (max, sum)
     float* part_o;          // workspace: [b][H_q][n_splits][128]
     float softmax_scale;

@@ -142,7 +142,8 @@ class Cache:
             self.buffers[name] = buf
             setattr(self.c, name, buf.data_ptr())
         ws = kivi_decode_workspace_bytes(layout)
-        self.workspace = torch.empty(max(ws, 16), dtype=torch.uint8, device=device)
+        # zero-filled once: the decode kernel keeps its split counters at zero between calls
+        self.workspace = torch.zeros(max(ws, 16), dtype=torch.uint8, device=device)
 
     # convenience typed views (tests compare these against the oracle)
     def view(self, name):
