@@ -57,12 +57,14 @@ __device__ __forceinline__ int ring_slot(int start, int i, int cap) {
     return s;
 }
 
-// LDS traffic between the lanes of one wavefront needs no hardware barrier (a wavefront's LDS
-// operations execute in order); this only stops the compiler from reordering across it.
+// LDS traffic between the lanes of one wavefront needs no hardware barrier and no wait: a
+// wavefront's LDS instructions execute in issue order, so a read issued after a write sees it.
+// This only keeps the compiler from moving memory operations across the point (a real fence
+// would also make the wave wait for all its outstanding global loads).
 __device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    asm volatile("" ::: "memory");
     __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    asm volatile("" ::: "memory");
 }
 
 // data-parallel-primitive lane moves (all source lanes are valid for these patterns)
@@ -270,6 +272,15 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
 
     WL& wl = sm_w[wave];
 
+    // the query loads go first: loads return in order, and phase 0 must not wait for the cache data
+    constexpr int kQPerThread = (REP * kHeadDim + 255) / 256;
+    __half qraw[kQPerThread];
+#pragma unroll
+    for (int k = 0; k < kQPerThread; ++k) {
+        const int i = min(tid + k * 256, REP * kHeadDim - 1);
+        qraw[k] = p.q[((int64_t)b * p.n_q_heads + hq0) * kHeadDim + i];
+    }
+
     // ---------------- region A: issue every load of the sub-split before anything else ---------
     uint32_t kw[kSlots][kLaneWords], vw[kSlots][kLaneWords];
     __half2 ks2[kSlots], vs2[kSlots], vz2[kSlots];
@@ -294,15 +305,19 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
         }
     }
 
-    // ---------------- phase 0: query operands ----------------
-    for (int i = tid; i < REP * kHeadDim; i += 256) {
-        const int hh = i / kHeadDim, c = i % kHeadDim;
-        const float x = p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]);
-        __half hi, lo;
-        split_hi_lo(x, hi, lo);
-        sm_q[hh][c] = x;
-        sm_qf[2 * hh][c] = hi;
-        sm_qf[2 * hh + 1][c] = lo;
+    // ---------------- phase 0: query operands (their loads were issued first, see above) --------
+#pragma unroll
+    for (int k = 0; k < kQPerThread; ++k) {
+        const int i = tid + k * 256;
+        if (i < REP * kHeadDim) {
+            const int hh = i / kHeadDim, c = i % kHeadDim;
+            const float x = p.softmax_scale * __half2float(qraw[k]);
+            __half hi, lo;
+            split_hi_lo(x, hi, lo);
+            sm_q[hh][c] = x;
+            sm_qf[2 * hh][c] = hi;
+            sm_qf[2 * hh + 1][c] = lo;
+        }
     }
     if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
     __syncthreads();
