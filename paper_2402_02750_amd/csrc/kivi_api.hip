@@ -304,7 +304,9 @@ int kivi_decode_attention(const kivi_layout_t* l, const kivi_cache_t* c, const v
     p.softmax_scale = softmax_scale;
     p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
     p.length = length;
-    const int path = l->decode_path == KIVI_DECODE_AUTO ? KIVI_DECODE_MFMA : l->decode_path;
+    // the matrix-core family covers up to 4 query heads per kv-head; 8 run on the vector ALUs
+    const int rep = l->n_q_heads / l->n_kv_heads;
+    const int path = (l->decode_path == KIVI_DECODE_VALU || rep > 4) ? KIVI_DECODE_VALU : KIVI_DECODE_MFMA;
     p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA ? kMfmaSplitTiles : kMaxSplitTiles);
     const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
     p.counters = static_cast<int32_t*>(workspace);

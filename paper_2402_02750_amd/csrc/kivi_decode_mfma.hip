@@ -14,18 +14,22 @@
 // exact fp16).  The fp16 residual rows are 5x the bytes per element, so they stay on the vector
 // ALUs.
 //
-// A workgroup (4 wavefronts) owns one context split of one (batch, kv-head) and all query heads
-// reading it; each wavefront takes every 4th tile of the split (4 tile slots) as an independent
-// sub-split with its own softmax maximum, so there is no barrier between logits and outputs.  In
-// a split whose tiles are all quantised ("region A") a wavefront issues every global load of its
-// sub-split before it computes anything and runs branch-free (slots past the end of the split
-// re-read the last tile and are masked): the scan is latency-bound otherwise.  The four
-// sub-splits are merged in LDS, one (m, l, o[128]) per query head goes to the workspace, and the
-// last workgroup of a (batch, kv-head) to finish merges the splits (a counter in the workspace
-// tells which one that is), so one launch does the whole attention.
+// The token axis of every (batch, kv-head) unit is cut into chunks of up to 16 tiles (4 tile slots
+// per wavefront, every 4th tile of the chunk).  The kernel is persistent: the grid is sized to what
+// the chip holds at once and each workgroup (4 wavefronts) walks a contiguous range of chunks.  A
+// wavefront keeps a running softmax maximum and un-normalised output across the chunks of a unit
+// (it rescales only when the maximum grows), and it requests the next chunk's packed data as soon
+// as the registers holding the current chunk's data have been consumed, so HBM requests are in
+// flight all the time -- the scan is latency-bound otherwise.  Chunks whose tiles are all quantised
+// run branch-free (slots past the end of the chunk re-read its last tile and are masked).  When a
+// workgroup leaves a unit it merges its four wavefronts in LDS; if it covered the whole unit it
+// writes the output, otherwise one (m, l, o[128]) per query head goes to the workspace and the
+// last workgroup to finish that unit merges the parts (a counter in the workspace tells which).
 #include "kivi_internal.h"
 
 #include <hip/hip_fp16.h>
+
+#include <algorithm>
 
 namespace kivi {
 namespace {
@@ -151,7 +155,7 @@ __device__ __forceinline__ void split_hi_lo(float x, __half& hi, __half& lo) {
 template <int REP>
 struct WaveLds {
     static constexpr int NC = 2 * REP;
-    static constexpr int kStageSlots = REP <= 2 ? 4 : (REP == 4 ? 2 : 1);   // tile slots staged at once
+    static constexpr int kStageSlots = REP <= 2 ? 2 : 1;   // tile slots staged at once (register pressure)
     static constexpr int kKSlot = NC * kKRow;          // halves per staged key-side operand
     static constexpr int kVSlot = 4 * NC * kVRow;      // halves per staged value-side operand
     static constexpr int kBHalves = kStageSlots * (kKSlot > kVSlot ? kKSlot : kVSlot);
@@ -244,144 +248,357 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
     __shared__ __align__(16) float sm_q[REP][kHeadDim];               // scale * q
     __shared__ __align__(16) __half sm_qf[NC][kKRow];                 // its hi/lo columns (z-term operand)
     __shared__ WL sm_w[4];
+    __shared__ __align__(16) float sm_r[4][REP][kHeadDim];            // vector-ALU (fp16 residual) outputs
+    __shared__ float sm_zs[4][REP][4];                                // value z-term sums per channel group
     __shared__ float sm_ml[4][REP][2];
     __shared__ int sm_last;
 
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 15, rq = lane >> 4;          // matrix column / row-quad (= k-quad for operands)
     const int ncol = n & (NC - 1);
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
     constexpr int kLaneWords = BITS * 2;
-
-    const bool region_a = split < p.plan.n_splits_a;
-    int tile0, tile1;
-    if (region_a) {
-        tile0 = split * p.plan.tiles_per_split_a;
-        tile1 = min(tile0 + p.plan.tiles_per_split_a, p.plan.tiles_a);
-    } else {
-        tile0 = p.plan.tiles_a + (split - p.plan.n_splits_a) * p.plan.tiles_per_split_b;
-        tile1 = min(tile0 + p.plan.tiles_per_split_b, p.plan.tiles_total);
-    }
-    const int n_tiles = tile1 - tile0;                // 1 .. 16
-    const int64_t unit = (int64_t)b * p.n_kv_heads + h;
-    const int hq0 = h * REP;
-    // slot i of this wavefront is tile  tile0 + wave + 4*i  (valid while wave + 4*i < n_tiles)
-    const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
-    const int64_t ubase = unit * p.cap_tiles + tile0;
-
     WL& wl = sm_w[wave];
 
-    // the query loads go first: loads return in order, and phase 0 must not wait for the cache data
-    constexpr int kQPerThread = (REP * kHeadDim + 255) / 256;
-    __half qraw[kQPerThread];
-#pragma unroll
-    for (int k = 0; k < kQPerThread; ++k) {
-        const int i = min(tid + k * 256, REP * kHeadDim - 1);
-        qraw[k] = p.q[((int64_t)b * p.n_q_heads + hq0) * kHeadDim + i];
-    }
+    const int n_a = p.plan.n_splits_a, n_b = p.plan.n_splits_b;   // chunks per unit: all-quantised / with fp16 rows
+    const int cpu = n_a + n_b;
+    // this workgroup's ranges in the two global chunk index spaces (unit-major)
+    const int first_a = blockIdx.x * p.chunks_per_wg_a, last_a = min(first_a + p.chunks_per_wg_a, p.total_chunks_a);
+    const int first_b = blockIdx.x * p.chunks_per_wg_b, last_b = min(first_b + p.chunks_per_wg_b, p.total_chunks_b);
 
-    // ---------------- region A: issue every load of the sub-split before anything else ---------
+    // registers holding the packed data of one all-quantised chunk (4 slots of this wavefront)
     uint32_t kw[kSlots][kLaneWords], vw[kSlots][kLaneWords];
     __half2 ks2[kSlots], vs2[kSlots], vz2[kSlots];
     half8 zf[4];
-    if (region_a) {
-        const int64_t zt_tile = ubase + min(wave + 4 * min(n, kSlots - 1), n_tiles - 1);   // A row n = slot n
+
+    // first tile and tile count of all-quantised chunk ck
+    auto chunk_a_geometry = [&](int ck, int& u, int& tile0, int& n_tiles) {
+        u = ck / n_a;
+        tile0 = (ck - u * n_a) * p.plan.tiles_per_split_a;
+        n_tiles = min(p.plan.tiles_per_split_a, p.plan.tiles_a - tile0);
+    };
+    auto chunk_tile = [&](int ck, int slot_or_row) -> int64_t {
+        int u, tile0, n_tiles;
+        chunk_a_geometry(ck, u, tile0, n_tiles);
+        return (int64_t)u * p.cap_tiles + tile0 + min(wave + 4 * slot_or_row, n_tiles - 1);
+    };
+    // requests for all-quantised chunk ck; one past this workgroup's range clears the registers instead
+    auto request_zero_rows = [&](int ck) {
+        if (ck >= last_a) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
+            return;
+        }
+        const int64_t tile = chunk_tile(ck, min(n, kSlots - 1));           // A row n = slot n
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            zf[ks] = *reinterpret_cast<const half8*>(p.k_zero + zt_tile * kHeadDim + ks * 32 + rq * 8);
+            zf[ks] = *reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8);
+    };
+    auto request_key_slot = [&](int ck, int i) {
+        if (ck >= last_a) {
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) {
-            const int64_t tile = ubase + min(wave + 4 * i, n_tiles - 1);
-            load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
-            ks2[i] = *reinterpret_cast<const __half2*>(p.k_scale + tile * kHeadDim + 2 * lane);
+            for (int k = 0; k < kLaneWords; ++k) kw[i][k] = 0u;
+            ks2[i] = __half2{};
+            return;
         }
+        const int64_t tile = chunk_tile(ck, i);
+        load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
+        ks2[i] = *reinterpret_cast<const __half2*>(p.k_scale + tile * kHeadDim + 2 * lane);
+    };
+    auto request_value_slot = [&](int ck, int i) {
+        if (ck >= last_a) {
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) {
-            const int64_t tile = ubase + min(wave + 4 * i, n_tiles - 1);
-            load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
-            vs2[i] = *reinterpret_cast<const __half2*>(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
-            vz2[i] = *reinterpret_cast<const __half2*>(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+            for (int k = 0; k < kLaneWords; ++k) vw[i][k] = 0u;
+            vs2[i] = vz2[i] = __half2{};
+            return;
         }
-    }
+        const int64_t tile = chunk_tile(ck, i);
+        load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
+        vs2[i] = *reinterpret_cast<const __half2*>(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
+        vz2[i] = *reinterpret_cast<const __half2*>(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+    };
 
-    // ---------------- phase 0: query operands (their loads were issued first, see above) --------
+    // per-wave running state of the current unit
+    float4v acc[8];
+    float zacc[REP][2], m_run[REP], l_lane[REP], qpf[REP][2];
+    auto reset_state = [&]() {
 #pragma unroll
-    for (int k = 0; k < kQPerThread; ++k) {
-        const int i = tid + k * 256;
-        if (i < REP * kHeadDim) {
+        for (int u = 0; u < 8; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int hh = 0; hh < REP; ++hh) {
+            zacc[hh][0] = zacc[hh][1] = 0.f;
+            m_run[hh] = -INFINITY;
+            l_lane[hh] = 0.f;
+        }
+        // fp16-residual (vector-ALU) outputs of the unit accumulate in this wavefront's LDS rows
+        for (int i = lane; i < REP * kHeadDim; i += 64) (&sm_r[wave][0][0])[i] = 0.f;
+    };
+
+    // ---- leave a unit: merge the four wavefronts, write the output or this workgroup's part ----
+    auto finish_unit = [&](int u, bool in_loop_b) {
+        const int hq0 = (u % p.n_kv_heads) * REP;
+        const int b = u / p.n_kv_heads;
+        // raw matrix-core outputs: column n of acc[u8] -> lr[n][channel]
+        if (n < NC) {
+#pragma unroll
+            for (int u8 = 0; u8 < 8; ++u8)
+                *reinterpret_cast<float4*>(&wl.lr[n][u8 * 16 + rq * 4]) =
+                    make_float4(acc[u8][0], acc[u8][1], acc[u8][2], acc[u8][3]);
+        }
+        // z-term sums over tokens: lanes of equal parity hold the same channel-group pair, so
+        // reduce with parity-preserving moves (xor 2, rotate by 4 and 8 inside a row, then rows)
+#pragma unroll
+        for (int hh = 0; hh < REP; ++hh) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                float zz = zacc[hh][k];
+                zz += dpp<kDppXor2>(zz); zz += dpp<kDppRor4>(zz); zz += dpp<kDppRor8>(zz);
+                zz += __shfl_xor(zz, 16); zz += __shfl_xor(zz, 32);
+                if (lane < 2) sm_zs[wave][hh][lane * 2 + k] = zz;      // lane 0: groups 0,1; lane 1: groups 2,3
+            }
+            const float l_w = wave_sum(l_lane[hh]);
+            if (lane == 0) { sm_ml[wave][hh][0] = m_run[hh]; sm_ml[wave][hh][1] = l_w; }
+        }
+        __syncthreads();
+
+        // workgroups contributing to unit u: those whose all-quantised range touches it, then those
+        // whose fp16-row range touches it
+        const int ga0 = n_a ? (u * n_a) / p.chunks_per_wg_a : 0;
+        const int parts_a = n_a ? ((u + 1) * n_a - 1) / p.chunks_per_wg_a - ga0 + 1 : 0;
+        const int gb0 = n_b ? (u * n_b) / p.chunks_per_wg_b : 0;
+        const int parts_b = n_b ? ((u + 1) * n_b - 1) / p.chunks_per_wg_b - gb0 + 1 : 0;
+        const int n_parts = parts_a + parts_b;
+        const int part = in_loop_b ? parts_a + (int)blockIdx.x - gb0 : (int)blockIdx.x - ga0;
+        const int row_stride = cpu;                               // workspace rows per (batch, query head)
+        for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
+            const int hh = idx / kHeadDim, c = idx % kHeadDim;
+            float m = -INFINITY;
+#pragma unroll
+            for (int wv = 0; wv < 4; ++wv) m = fmaxf(m, sm_ml[wv][hh][0]);
+            float l = 0.f, o = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < 4; ++wv) {
+                const float mw = sm_ml[wv][hh][0];
+                if (mw > -INFINITY) {
+                    const float wgt = __expf(mw - m);
+                    const float ow = fmaf(sm_w[wv].lr[2 * hh][c] + sm_w[wv].lr[2 * hh + 1][c], kUnscale,
+                                          sm_zs[wv][hh][c >> 5]) + sm_r[wv][hh][c];
+                    l = fmaf(sm_ml[wv][hh][1], wgt, l);
+                    o = fmaf(ow, wgt, o);
+                }
+            }
+            const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
+            if (n_parts == 1) {
+                p.out[row * kHeadDim + c] = o / l;
+            } else {
+                // device-scope stores: they go through to memory, no cache flush is needed to publish them
+                device_store(p.part_o + (row * row_stride + part) * kHeadDim + c, o);
+                if (c == 0) {
+                    device_store(p.part_ml + (row * row_stride + part) * 2 + 0, m);
+                    device_store(p.part_ml + (row * row_stride + part) * 2 + 1, l);
+                }
+            }
+        }
+        if (n_parts > 1) {
+            // the last workgroup to finish this unit merges the parts
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // the stores above are acknowledged
+            __syncthreads();
+            if (tid == 0) {
+                const int done = __hip_atomic_fetch_add(p.counters + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                sm_last = (done == n_parts - 1);
+            }
+            __syncthreads();
+            if (sm_last) {
+                for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
+                    const int hh = idx / kHeadDim, c = idx % kHeadDim;
+                    const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
+                    const float* ml = p.part_ml + row * row_stride * 2;
+                    const float* po = p.part_o + row * row_stride * kHeadDim;
+                    float m = -INFINITY;
+                    for (int i = 0; i < n_parts; ++i) m = fmaxf(m, device_load(ml + 2 * i));
+                    float l = 0.f, o = 0.f;
+                    for (int i = 0; i < n_parts; ++i) {
+                        const float wgt = __expf(device_load(ml + 2 * i) - m);
+                        l = fmaf(device_load(ml + 2 * i + 1), wgt, l);
+                        o = fmaf(device_load(po + (int64_t)i * kHeadDim + c), wgt, o);
+                    }
+                    p.out[row * kHeadDim + c] = o / l;
+                }
+                if (tid == 0) __hip_atomic_store(p.counters + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __syncthreads();          // LDS is reused by the next unit
+    };
+
+    // ---- enter a unit: query operands ----
+    auto enter_unit = [&](int u) {
+        const int hq0 = (u % p.n_kv_heads) * REP;
+        const int b = u / p.n_kv_heads;
+        for (int i = tid; i < REP * kHeadDim; i += 256) {
             const int hh = i / kHeadDim, c = i % kHeadDim;
-            const float x = p.softmax_scale * __half2float(qraw[k]);
+            const float x = p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]);
             __half hi, lo;
             split_hi_lo(x, hi, lo);
             sm_q[hh][c] = x;
             sm_qf[2 * hh][c] = hi;
             sm_qf[2 * hh + 1][c] = lo;
         }
-    }
-    if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
-    __syncthreads();
-
-    // per-lane key-side query factors: channels 2*lane, 2*lane+1 times 1/position factor
-    float qpf[REP][2];
-    {
+        __syncthreads();
+        // per-lane key-side query factors: channels 2*lane, 2*lane+1 times 1/position factor
         const float pf = inv_pos_factor<BITS>(lane & 3);
 #pragma unroll
         for (int hh = 0; hh < REP; ++hh) {
             qpf[hh][0] = sm_q[hh][2 * lane] * pf;
             qpf[hh][1] = sm_q[hh][2 * lane + 1] * pf;
         }
+        reset_state();
+    };
+
+    // Probabilities of the wave's 128 token slots against the running maximum (2 slots per lane);
+    // rescales the running state when the maximum grows.
+    auto softmax_step = [&](int cnt) {
+        {
+            const int slot = lane >> 4;
+            const bool live = slot < cnt;
+            float a0[REP], a1[REP], scale_lane = 1.f;
+            bool any_rescale = false;
+#pragma unroll
+            for (int hh = 0; hh < REP; ++hh) {
+                const float2 hi = *reinterpret_cast<const float2*>(&wl.lr[2 * hh][2 * lane]);
+                const float2 lo = *reinterpret_cast<const float2*>(&wl.lr[2 * hh + 1][2 * lane]);
+                const float zt = wl.zt[2 * hh][slot] + wl.zt[2 * hh + 1][slot];
+                a0[hh] = live ? fmaf(hi.x + lo.x, kUnscale, zt) : -INFINITY;
+                a1[hh] = live ? fmaf(hi.y + lo.y, kUnscale, zt) : -INFINITY;
+                const float mx = wave_max(fmaxf(a0[hh], a1[hh]));
+                if (mx > m_run[hh]) {                       // wave-uniform: the running maximum grows
+                    const float f = __expf(m_run[hh] - mx); // 0 on the first chunk (m_run = -inf)
+                    l_lane[hh] *= f;
+                    zacc[hh][0] *= f; zacc[hh][1] *= f;
+                    sm_r[wave][hh][lane] *= f; sm_r[wave][hh][lane + 64] *= f;
+                    if ((n >> 1) == hh) scale_lane = f;
+                    any_rescale = true;
+                    m_run[hh] = mx;
+                }
+            }
+            if (any_rescale) {
+#pragma unroll
+                for (int u8 = 0; u8 < 8; ++u8)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[u8][j] *= scale_lane;
+            }
+#pragma unroll
+            for (int hh = 0; hh < REP; ++hh) {
+                const float ms = m_run[hh] == -INFINITY ? 0.f : m_run[hh];
+                const float p0 = __expf(a0[hh] - ms), p1 = __expf(a1[hh] - ms);
+                *reinterpret_cast<float2*>(&wl.lr[2 * hh][2 * lane]) = make_float2(p0, p1);
+                l_lane[hh] += p0 + p1;
+            }
+        }
+        wave_lds_sync();
+
+    };
+
+    int cur_unit = -1;
+
+    // ================= loop 1: all-quantised chunks, software-pipelined =================
+    if (first_a < last_a) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
+        request_zero_rows(first_a);
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) request_key_slot(first_a, i);
+#pragma unroll
+        for (int i = 0; i < kSlots; ++i) request_value_slot(first_a, i);
+        for (int ck = first_a; ck < last_a; ++ck) {
+            int u, tile0, n_tiles;
+            chunk_a_geometry(ck, u, tile0, n_tiles);
+            if (u != cur_unit) {
+                if (cur_unit >= 0) finish_unit(cur_unit, false);
+                enter_unit(u);
+                cur_unit = u;
+            }
+            const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;     // valid slots of this wavefront
+            // key z-terms of the wave's four slots: one 16x16x128 product
+            {
+                float4v d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[ncol][ks * 32 + rq * 8]);
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(zf[ks], bq, d, 0, 0, 0);
+                }
+                // d[j]: slot rq*4 + j (rows 0..3 are the wave's slots), column n
+                if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
+            }
+            request_zero_rows(ck + 1);
+
+            // ---- phase 1: raw logits ----
+#pragma unroll
+            for (int c0 = 0; c0 < kSlots; c0 += SS) {
+#pragma unroll
+                for (int s = 0; s < SS; ++s) stage_key_operand<REP>(wl.b + s * WL::kKSlot, ks2[c0 + s], qpf, lane);
+                wave_lds_sync();
+#pragma unroll
+                for (int s = 0; s < SS; ++s) {
+                    key_tile_mfma<BITS, REP>(kw[c0 + s], wl.b + s * WL::kKSlot, wl.lr, c0 + s, lane);
+                    request_key_slot(ck + 1, c0 + s);          // the slot's registers are free again
+                }
+                wave_lds_sync();
+            }
+            wave_lds_sync();
+            softmax_step(cnt);
+            wave_lds_sync();
+            // ---- phase 3: outputs ----
+#pragma unroll
+            for (int c0 = 0; c0 < kSlots; c0 += SS) {
+#pragma unroll
+                for (int s = 0; s < SS; ++s)
+                    stage_value_operand<BITS, REP>(wl.b + s * WL::kVSlot, vs2[c0 + s], vz2[c0 + s],
+                                                   c0 + s < cnt ? kTileTokens : 0, wl.lr, c0 + s, zacc, lane);
+                wave_lds_sync();
+#pragma unroll
+                for (int s = 0; s < SS; ++s) {
+                    value_tile_mfma<BITS, REP>(vw[c0 + s], wl.b + s * WL::kVSlot, acc, lane);
+                    request_value_slot(ck + 1, c0 + s);
+                }
+                wave_lds_sync();
+            }
+            wave_lds_sync();
+        }
+        finish_unit(cur_unit, false);
+        cur_unit = -1;
     }
 
-    // how many of the wave's tiles are quantised key tiles (they come first in token order)
-    int cnt_kq = cnt;
-    if (!region_a) {
-        cnt_kq = 0;
+    // ================= loop 2: chunks that hold fp16 rows (each loads its own data) =================
+    for (int ck = first_b; ck < last_b; ++ck) {
+        const int u = ck / n_b;
+        const int tile0 = p.plan.tiles_a + (ck - u * n_b) * p.plan.tiles_per_split_b;
+        const int n_tiles = min(p.plan.tiles_per_split_b, p.plan.tiles_total - tile0);
+        if (u != cur_unit) {
+            if (cur_unit >= 0) finish_unit(cur_unit, true);
+            enter_unit(u);
+            cur_unit = u;
+        }
+        const int64_t unit = u;
+        const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
+        const int64_t ubase = unit * p.cap_tiles + tile0;
+        if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
+        // how many of the wave's tiles are quantised key tiles (they come first in token order)
+        int cnt_kq = 0;
         for (int i = 0; i < cnt; ++i) cnt_kq += ((tile0 + wave + 4 * i) * kTileTokens < p.n_kq) ? 1 : 0;
         if (cnt_kq > 0) {
             const __half* zrow = p.k_zero + (ubase + wave + 4 * min(n, cnt_kq - 1)) * kHeadDim;
+            float4v d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) zf[ks] = *reinterpret_cast<const half8*>(zrow + ks * 32 + rq * 8);
-        }
-    }
-
-    // ---------------- key z-terms of the wave's quantised tiles: one 16x16x128 product ----------
-    if (cnt_kq > 0) {
-        float4v d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[ncol][ks * 32 + rq * 8]);
-            d = __builtin_amdgcn_mfma_f32_16x16x32_f16(zf[ks], bq, d, 0, 0, 0);
-        }
-        // d[j]: slot rq*4 + j (rows 0..3 are the wave's slots), column n
-        if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
-    }
-
-    float4v acc[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
-    float zacc[REP][2], racc[REP][8];
-#pragma unroll
-    for (int hh = 0; hh < REP; ++hh) {
-        zacc[hh][0] = zacc[hh][1] = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) racc[hh][e] = 0.f;
-    }
-
-    // ---------------- phase 1: raw logits of the wave's tiles ----------------
-    if (region_a) {
-#pragma unroll
-        for (int c0 = 0; c0 < kSlots; c0 += SS) {
-#pragma unroll
-            for (int s = 0; s < SS; ++s) stage_key_operand<REP>(wl.b + s * WL::kKSlot, ks2[c0 + s], qpf, lane);
+            for (int ks = 0; ks < 4; ++ks) {
+                const half8 za = *reinterpret_cast<const half8*>(zrow + ks * 32 + rq * 8);
+                const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[ncol][ks * 32 + rq * 8]);
+                d = __builtin_amdgcn_mfma_f32_16x16x32_f16(za, bq, d, 0, 0, 0);
+            }
             wave_lds_sync();
-#pragma unroll
-            for (int s = 0; s < SS; ++s)
-                key_tile_mfma<BITS, REP>(kw[c0 + s], wl.b + s * WL::kKSlot, wl.lr, c0 + s, lane);
-            wave_lds_sync();
+            if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
         }
-    } else {
-        for (int i = 0; i < cnt; ++i) {
+        // ---- phase 1: raw logits ----
+            for (int i = 0; i < cnt; ++i) {
             const int tile = tile0 + wave + 4 * i;
             const int tt = tile * kTileTokens;
             if (tt < p.n_kq) {
@@ -434,45 +651,16 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
                 }
             }
         }
-    }
-    wave_lds_sync();
-
-    // ---------------- phase 2: softmax of the wave's sub-split (2 token slots per lane) ---------
-    float m_w[REP], l_w[REP];
-    {
-        const int slot = lane >> 4;
-        const bool live = slot < cnt;
+        wave_lds_sync();
+        softmax_step(cnt);
+        wave_lds_sync();
+        // ---- phase 3: outputs ----
+        {
+            float racc[REP][8];
 #pragma unroll
-        for (int hh = 0; hh < REP; ++hh) {
-            const float2 hi = *reinterpret_cast<const float2*>(&wl.lr[2 * hh][2 * lane]);
-            const float2 lo = *reinterpret_cast<const float2*>(&wl.lr[2 * hh + 1][2 * lane]);
-            const float zt = wl.zt[2 * hh][slot] + wl.zt[2 * hh + 1][slot];
-            const float a0 = live ? fmaf(hi.x + lo.x, kUnscale, zt) : -INFINITY;
-            const float a1 = live ? fmaf(hi.y + lo.y, kUnscale, zt) : -INFINITY;
-            const float mx = wave_max(fmaxf(a0, a1));
-            const float ms = mx == -INFINITY ? 0.f : mx;
-            const float p0 = __expf(a0 - ms), p1 = __expf(a1 - ms);
-            *reinterpret_cast<float2*>(&wl.lr[2 * hh][2 * lane]) = make_float2(p0, p1);
-            m_w[hh] = mx;
-            l_w[hh] = wave_sum(p0 + p1);
-        }
-    }
-    wave_lds_sync();
-
-    // ---------------- phase 3: outputs of the wave's tiles ----------------
-    if (region_a) {
+        for (int hh = 0; hh < REP; ++hh)
 #pragma unroll
-        for (int c0 = 0; c0 < kSlots; c0 += SS) {
-#pragma unroll
-            for (int s = 0; s < SS; ++s)
-                stage_value_operand<BITS, REP>(wl.b + s * WL::kVSlot, vs2[c0 + s], vz2[c0 + s],
-                                               c0 + s < cnt ? kTileTokens : 0, wl.lr, c0 + s, zacc, lane);
-            wave_lds_sync();
-#pragma unroll
-            for (int s = 0; s < SS; ++s) value_tile_mfma<BITS, REP>(vw[c0 + s], wl.b + s * WL::kVSlot, acc, lane);
-            wave_lds_sync();
-        }
-    } else {
+            for (int e = 0; e < 8; ++e) racc[hh][e] = 0.f;
         for (int i = 0; i < cnt; ++i) {
             const int tile = tile0 + wave + 4 * i;
             const int tt = tile * kTileTokens;
@@ -516,120 +704,62 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
                 }
             }
         }
-    }
-    wave_lds_sync();
-
-    // ---------------- wave results -> LDS: the lo column of a head becomes its output row -------
-    {
-        // z-term sums over tokens: lanes of equal parity hold the same channel-group pair, so
-        // reduce with parity-preserving moves (xor 2, rotate by 4 and 8 inside a row, then rows)
-        float zs[4] = {0.f, 0.f, 0.f, 0.f};
+        // lane (seg, row) holds channels seg*8.. of every 4th row: add the four row groups into LDS
+        wave_lds_sync();
 #pragma unroll
         for (int hh = 0; hh < REP; ++hh) {
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                float zz = zacc[hh][k];
-                zz += dpp<kDppXor2>(zz); zz += dpp<kDppRor4>(zz); zz += dpp<kDppRor8>(zz);
-                zz += __shfl_xor(zz, 16); zz += __shfl_xor(zz, 32);
-                const float other = dpp<kDppXor1>(zz);          // the other parity's pair of groups
-                const bool odd = lane & 1;
-                if ((n >> 1) == hh) { zs[k] = odd ? other : zz; zs[2 + k] = odd ? zz : other; }
+            for (int e = 0; e < 8; ++e) {
+                float rr = racc[hh][e];
+                rr += __shfl_xor(rr, 16); rr += __shfl_xor(rr, 32);
+                racc[hh][e] = rr;
+            }
+            if (lane < 16) {
+                float* dst = &sm_r[wave][hh][lane * 8];
+                float4 a = *reinterpret_cast<float4*>(dst), c = *reinterpret_cast<float4*>(dst + 4);
+                a.x += racc[hh][0]; a.y += racc[hh][1]; a.z += racc[hh][2]; a.w += racc[hh][3];
+                c.x += racc[hh][4]; c.y += racc[hh][5]; c.z += racc[hh][6]; c.w += racc[hh][7];
+                *reinterpret_cast<float4*>(dst) = a;
+                *reinterpret_cast<float4*>(dst + 4) = c;
             }
         }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            float v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = acc[u][j] + dpp<kDppXor1>(acc[u][j]);   // hi + lo column
-            if (!(n & 1) && n < NC) {
-                const float z = zs[u >> 1];
-                *reinterpret_cast<float4*>(&wl.lr[n + 1][u * 16 + rq * 4]) = make_float4(
-                    fmaf(v[0], kUnscale, z), fmaf(v[1], kUnscale, z), fmaf(v[2], kUnscale, z), fmaf(v[3], kUnscale, z));
-            }
         }
-        if (!region_a) {
-            wave_lds_sync();
-#pragma unroll
-            for (int hh = 0; hh < REP; ++hh) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    float rr = racc[hh][e];
-                    rr += __shfl_xor(rr, 16); rr += __shfl_xor(rr, 32);
-                    racc[hh][e] = rr;
-                }
-                if (lane < 16) {
-                    float* dst = &wl.lr[2 * hh + 1][lane * 8];
-                    float4 a = *reinterpret_cast<float4*>(dst), c = *reinterpret_cast<float4*>(dst + 4);
-                    a.x += racc[hh][0]; a.y += racc[hh][1]; a.z += racc[hh][2]; a.w += racc[hh][3];
-                    c.x += racc[hh][4]; c.y += racc[hh][5]; c.z += racc[hh][6]; c.w += racc[hh][7];
-                    *reinterpret_cast<float4*>(dst) = a;
-                    *reinterpret_cast<float4*>(dst + 4) = c;
-                }
-            }
-        }
-        if (lane == 0) {
-#pragma unroll
-            for (int hh = 0; hh < REP; ++hh) { sm_ml[wave][hh][0] = m_w[hh]; sm_ml[wave][hh][1] = l_w[hh]; }
-        }
+        wave_lds_sync();
     }
-    __syncthreads();
+    if (cur_unit >= 0) finish_unit(cur_unit, true);
+}
 
-    // ---------------- merge the four sub-splits ----------------
-    const int n_splits = p.plan.n_splits();
-    for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
-        const int hh = idx / kHeadDim, c = idx % kHeadDim;
-        float m = -INFINITY;
-#pragma unroll
-        for (int wv = 0; wv < 4; ++wv) m = fmaxf(m, sm_ml[wv][hh][0]);
-        float l = 0.f, o = 0.f;
-#pragma unroll
-        for (int wv = 0; wv < 4; ++wv) {
-            const float mw = sm_ml[wv][hh][0];
-            if (mw > -INFINITY) {
-                const float wgt = __expf(mw - m);
-                l = fmaf(sm_ml[wv][hh][1], wgt, l);
-                o = fmaf(sm_w[wv].lr[2 * hh + 1][c], wgt, o);
-            }
-        }
-        const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
-        if (n_splits == 1) {
-            p.out[row * kHeadDim + c] = o / l;
-        } else {
-            // device-scope stores: they go through to memory, no cache flush is needed to publish them
-            device_store(p.part_o + (row * n_splits + split) * kHeadDim + c, o);
-            if (c == 0) {
-                device_store(p.part_ml + (row * n_splits + split) * 2 + 0, m);
-                device_store(p.part_ml + (row * n_splits + split) * 2 + 1, l);
-            }
-        }
+// Workgroups the chip holds at once for one instantiation (occupancy query, cached).
+template <int BITS, int REP>
+int resident_workgroups() {
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP>, 256, 0) != hipSuccess ||
+            cus <= 0 || per_cu <= 0)
+            return 256;
+        cached = cus * per_cu;
     }
-    if (n_splits == 1) return;
+    return cached;
+}
 
-    // ---------------- the last workgroup of this (batch, kv-head) merges the splits ------------
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // wait until the stores above are acknowledged
-    __syncthreads();
-    if (tid == 0) {
-        const int done = __hip_atomic_fetch_add(p.counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sm_last = (done == n_splits - 1);
-    }
-    __syncthreads();
-    if (!sm_last) return;
-    for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
-        const int hh = idx / kHeadDim, c = idx % kHeadDim;
-        const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
-        const float* ml = p.part_ml + row * n_splits * 2;
-        const float* po = p.part_o + row * n_splits * kHeadDim;
-        float m = -INFINITY;
-        for (int i = 0; i < n_splits; ++i) m = fmaxf(m, device_load(ml + 2 * i));
-        float l = 0.f, o = 0.f;
-        for (int i = 0; i < n_splits; ++i) {
-            const float wgt = __expf(device_load(ml + 2 * i) - m);
-            l = fmaf(device_load(ml + 2 * i + 1), wgt, l);
-            o = fmaf(device_load(po + (int64_t)i * kHeadDim + c), wgt, o);
-        }
-        p.out[row * kHeadDim + c] = o / l;
-    }
-    if (tid == 0) __hip_atomic_store(p.counters + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+template <int BITS, int REP>
+hipError_t launch_one(DecodeParams p, hipStream_t stream) {
+    const int64_t units = (int64_t)p.batch * p.n_kv_heads;
+    const int64_t total_a = units * p.plan.n_splits_a, total_b = units * p.plan.n_splits_b;
+    if (total_a + total_b > 0x7fffffff) return hipErrorInvalidValue;
+    // every resident workgroup gets an equal share of both kinds of chunks
+    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP>(), std::max(total_a, total_b)));
+    p.total_chunks_a = (int)total_a;
+    p.total_chunks_b = (int)total_b;
+    p.chunks_per_wg_a = (int)std::max<int64_t>(1, (total_a + slots - 1) / slots);
+    p.chunks_per_wg_b = (int)std::max<int64_t>(1, (total_b + slots - 1) / slots);
+    const int grid = (int)std::max((total_a + p.chunks_per_wg_a - 1) / p.chunks_per_wg_a,
+                                   (total_b + p.chunks_per_wg_b - 1) / p.chunks_per_wg_b);
+    decode_mfma_kernel<BITS, REP><<<grid, 256, 0, stream>>>(p);
+    return hipGetLastError();
 }
 
 template <int BITS>
@@ -637,15 +767,12 @@ hipError_t launch_bits(const DecodeParams& p, hipStream_t stream) {
     const int rep = p.n_q_heads / p.n_kv_heads;
     if (p.plan.tiles_per_split_a > kMfmaSplitTiles || p.plan.tiles_per_split_b > kMfmaSplitTiles)
         return hipErrorInvalidValue;
-    dim3 grid(p.plan.n_splits(), p.n_kv_heads, p.batch), block(256);
     switch (rep) {
-        case 1: decode_mfma_kernel<BITS, 1><<<grid, block, 0, stream>>>(p); break;
-        case 2: decode_mfma_kernel<BITS, 2><<<grid, block, 0, stream>>>(p); break;
-        case 4: decode_mfma_kernel<BITS, 4><<<grid, block, 0, stream>>>(p); break;
-        case 8: decode_mfma_kernel<BITS, 8><<<grid, block, 0, stream>>>(p); break;
-        default: return hipErrorNotSupported;
+        case 1: return launch_one<BITS, 1>(p, stream);
+        case 2: return launch_one<BITS, 2>(p, stream);
+        case 4: return launch_one<BITS, 4>(p, stream);
+        default: return hipErrorNotSupported;   // 8 query heads per kv-head: vector-ALU family
     }
-    return hipGetLastError();
 }
 
 }  // namespace

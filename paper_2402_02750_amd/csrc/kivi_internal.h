@@ -82,6 +82,9 @@ struct DecodeParams {
     float softmax_scale;
     int32_t batch, n_q_heads, n_kv_heads, bits, length;
     SplitPlan plan;
+    // persistent matrix-core kernel: chunk = (unit, split) in two unit-major index spaces (all-quantised
+    // splits / splits with fp16 rows); workgroup g walks [g*cpw, (g+1)*cpw) of each
+    int32_t total_chunks_a, chunks_per_wg_a, total_chunks_b, chunks_per_wg_b;
 };
 
 // launchers (each defined next to its kernels); they return hipGetLastError() after the launch
