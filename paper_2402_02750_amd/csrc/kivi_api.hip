@@ -80,7 +80,13 @@ SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, int max_til
     const int packed_per_tile = kTileTokens * 2 * (kHeadDim * l->bits / 8 + 16);
     const int fp16_per_tile = kTileTokens * 2 * kHeadDim * 2;
     const int tiles_b = s.tiles_total - s.tiles_a;
-    const int tps_b_max = std::max(1, std::min(8, s.tiles_per_split_a * packed_per_tile / fp16_per_tile));
+    int tps_b_max = std::max(1, std::min(8, s.tiles_per_split_a * packed_per_tile / fp16_per_tile));
+    if (max_tiles == kMfmaSplitTiles) {
+        // persistent matrix-core kernel: ~512 resident workgroups each take an equal count of fp16-row
+        // chunks, so make the chunks as long as possible while every workgroup still gets one
+        // (4 tiles = one per wavefront is the natural size)
+        tps_b_max = (int)std::max<int64_t>(1, std::min<int64_t>(kMfmaSplitTiles, units * tiles_b / 512));
+    }
     s.n_splits_b = ceil_div(tiles_b, tps_b_max);
     s.tiles_per_split_b = s.n_splits_b ? ceil_div(tiles_b, s.n_splits_b) : 1;     // even out the pieces
     s.n_splits_a = ceil_div(s.tiles_a, s.tiles_per_split_a);

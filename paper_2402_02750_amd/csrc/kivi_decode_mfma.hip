@@ -253,7 +253,8 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
     __shared__ float sm_ml[4][REP][2];
     __shared__ int sm_last;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps tile arithmetic scalar
     const int n = lane & 15, rq = lane >> 4;          // matrix column / row-quad (= k-quad for operands)
     const int ncol = n & (NC - 1);
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
@@ -271,48 +272,56 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
     __half2 ks2[kSlots], vs2[kSlots], vz2[kSlots];
     half8 zf[4];
 
-    // first tile and tile count of all-quantised chunk ck
-    auto chunk_a_geometry = [&](int ck, int& u, int& tile0, int& n_tiles) {
-        u = ck / n_a;
-        tile0 = (ck - u * n_a) * p.plan.tiles_per_split_a;
-        n_tiles = min(p.plan.tiles_per_split_a, p.plan.tiles_a - tile0);
+    // The all-quantised chunk whose data is being requested ("next"): unit, chunk index inside the
+    // unit, and derived tile range.  Advanced without divisions.
+    int nx_u = 0, nx_j = 0, nx_nt = 1;
+    bool nx_ok = false;
+    int64_t nx_base = 0;
+    auto set_next = [&](int ck, bool first_call) {
+        nx_ok = ck < last_a;
+        if (first_call) {
+            nx_u = n_a ? ck / n_a : 0;
+            nx_j = ck - nx_u * n_a;
+        } else if (++nx_j == n_a) {
+            nx_j = 0;
+            ++nx_u;
+        }
+        const int tile0 = nx_j * p.plan.tiles_per_split_a;
+        nx_nt = min(p.plan.tiles_per_split_a, p.plan.tiles_a - tile0);
+        nx_base = (int64_t)nx_u * p.cap_tiles + tile0;
     };
-    auto chunk_tile = [&](int ck, int slot_or_row) -> int64_t {
-        int u, tile0, n_tiles;
-        chunk_a_geometry(ck, u, tile0, n_tiles);
-        return (int64_t)u * p.cap_tiles + tile0 + min(wave + 4 * slot_or_row, n_tiles - 1);
-    };
+    auto chunk_tile = [&](int slot_or_row) -> int64_t { return nx_base + min(wave + 4 * slot_or_row, nx_nt - 1); };
     // requests for all-quantised chunk ck; one past this workgroup's range clears the registers instead
-    auto request_zero_rows = [&](int ck) {
-        if (ck >= last_a) {
+    auto request_zero_rows = [&]() {
+        if (!nx_ok) {
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
             return;
         }
-        const int64_t tile = chunk_tile(ck, min(n, kSlots - 1));           // A row n = slot n
+        const int64_t tile = nx_base + min(wave + 4 * min(n, kSlots - 1), nx_nt - 1);   // A row n = slot n
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
             zf[ks] = *reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8);
     };
-    auto request_key_slot = [&](int ck, int i) {
-        if (ck >= last_a) {
+    auto request_key_slot = [&](int i) {
+        if (!nx_ok) {
 #pragma unroll
             for (int k = 0; k < kLaneWords; ++k) kw[i][k] = 0u;
             ks2[i] = __half2{};
             return;
         }
-        const int64_t tile = chunk_tile(ck, i);
+        const int64_t tile = chunk_tile(i);
         load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
         ks2[i] = *reinterpret_cast<const __half2*>(p.k_scale + tile * kHeadDim + 2 * lane);
     };
-    auto request_value_slot = [&](int ck, int i) {
-        if (ck >= last_a) {
+    auto request_value_slot = [&](int i) {
+        if (!nx_ok) {
 #pragma unroll
             for (int k = 0; k < kLaneWords; ++k) vw[i][k] = 0u;
             vs2[i] = vz2[i] = __half2{};
             return;
         }
-        const int64_t tile = chunk_tile(ck, i);
+        const int64_t tile = chunk_tile(i);
         load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
         vs2[i] = *reinterpret_cast<const __half2*>(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
         vz2[i] = *reinterpret_cast<const __half2*>(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
@@ -504,14 +513,15 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
     if (first_a < last_a) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
-        request_zero_rows(first_a);
+        set_next(first_a, true);
+        request_zero_rows();
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) request_key_slot(first_a, i);
+        for (int i = 0; i < kSlots; ++i) request_key_slot(i);
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) request_value_slot(first_a, i);
+        for (int i = 0; i < kSlots; ++i) request_value_slot(i);
         for (int ck = first_a; ck < last_a; ++ck) {
-            int u, tile0, n_tiles;
-            chunk_a_geometry(ck, u, tile0, n_tiles);
+            const int u = nx_u, n_tiles = nx_nt;         // the chunk requested last is the one processed now
+            set_next(ck + 1, false);
             if (u != cur_unit) {
                 if (cur_unit >= 0) finish_unit(cur_unit, false);
                 enter_unit(u);
@@ -529,7 +539,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
                 // d[j]: slot rq*4 + j (rows 0..3 are the wave's slots), column n
                 if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
             }
-            request_zero_rows(ck + 1);
+            request_zero_rows();
 
             // ---- phase 1: raw logits ----
 #pragma unroll
@@ -540,7 +550,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
                 for (int s = 0; s < SS; ++s) {
                     key_tile_mfma<BITS, REP>(kw[c0 + s], wl.b + s * WL::kKSlot, wl.lr, c0 + s, lane);
-                    request_key_slot(ck + 1, c0 + s);          // the slot's registers are free again
+                    request_key_slot(c0 + s);                  // the slot's registers are free again
                 }
                 wave_lds_sync();
             }
@@ -558,7 +568,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
                 for (int s = 0; s < SS; ++s) {
                     value_tile_mfma<BITS, REP>(vw[c0 + s], wl.b + s * WL::kVSlot, acc, lane);
-                    request_value_slot(ck + 1, c0 + s);
+                    request_value_slot(c0 + s);
                 }
                 wave_lds_sync();
             }
@@ -597,8 +607,22 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
             wave_lds_sync();
             if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
         }
+        // fp16 value rows of the wave's first tile are requested now, ahead of the logits
+        // lane (seg, row): row j*4 + (lane >> 4) of the tile, channels (lane & 15)*8 ..; clamped rows are not used
+        auto load_value_row = [&](int tt, int j) -> Half8 {
+            const int t = min(max(tt + j * 4 + (lane >> 4), p.n_vq), p.length - 1);
+            const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
+            return *reinterpret_cast<const Half8*>(p.v_resid + (unit * p.cap_r + slot) * kHeadDim + (lane & 15) * 8);
+        };
+        Half8 vr0[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vr0[j] = Half8{};
+        if (cnt > 0 && p.n_vr > 0 && p.n_vq < (tile0 + wave + 1) * kTileTokens) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vr0[j] = load_value_row((tile0 + wave) * kTileTokens, j);
+        }
         // ---- phase 1: raw logits ----
-            for (int i = 0; i < cnt; ++i) {
+        for (int i = 0; i < cnt; ++i) {
             const int tile = tile0 + wave + 4 * i;
             const int tt = tile * kTileTokens;
             if (tt < p.n_kq) {
@@ -620,32 +644,29 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
                 for (int hh = 0; hh < REP; ++hh)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) qv[hh][e] = sm_q[hh][seg * 8 + e];
+                Half8 kr[8];
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    Half8 kr[4];
+                for (int j = 0; j < 8; ++j) {        // every row load of the tile first; rows past the end re-read the last row
+                    const int t = min(tt + j * 4 + row, p.length - 1);
+                    const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
+                    kr[j] = *reinterpret_cast<const Half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
+                }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {    // rows past the end re-read the last row
-                        const int t = min(tt + (half * 4 + j) * 4 + row, p.length - 1);
-                        const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
-                        kr[j] = *reinterpret_cast<const Half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
-                    }
+                for (int j = 0; j < 8; ++j) {
+                    const int tl = j * 4 + row;
+                    const bool valid = tt + tl < p.length;
+                    float k[8];
+                    unpack8(kr[j], k);
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int tl = (half * 4 + j) * 4 + row;
-                        const bool valid = tt + tl < p.length;
-                        float k[8];
-                        unpack8(kr[j], k);
+                    for (int hh = 0; hh < REP; ++hh) {
+                        float a = 0.f;
 #pragma unroll
-                        for (int hh = 0; hh < REP; ++hh) {
-                            float a = 0.f;
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) a = fmaf(qv[hh][e], k[e], a);
-                            a += dpp<kDppXor1>(a); a += dpp<kDppXor2>(a);
-                            a += dpp<kDppHalfMirror>(a); a += dpp<kDppMirror>(a);
-                            if (seg == 0) {
-                                wl.lr[2 * hh][i * kTileTokens + tl] = valid ? a * kDownscale : -INFINITY;
-                                wl.lr[2 * hh + 1][i * kTileTokens + tl] = 0.f;
-                            }
+                        for (int e = 0; e < 8; ++e) a = fmaf(qv[hh][e], k[e], a);
+                        a += dpp<kDppXor1>(a); a += dpp<kDppXor2>(a);
+                        a += dpp<kDppHalfMirror>(a); a += dpp<kDppMirror>(a);
+                        if (seg == 0) {
+                            wl.lr[2 * hh][i * kTileTokens + tl] = valid ? a * kDownscale : -INFINITY;
+                            wl.lr[2 * hh + 1][i * kTileTokens + tl] = 0.f;
                         }
                     }
                 }
@@ -678,28 +699,25 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
             }
             if (n_vq_here < kTileTokens && p.n_vr > 0) {
                 // fp16 residual values on the vector ALUs: lane (seg, row)
-                const int seg = lane & 15, row = lane >> 4;
+                Half8 vr[8];
+                if (i == 0) {
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    Half8 vr[4];
+                    for (int j = 0; j < 8; ++j) vr[j] = vr0[j];      // requested before the logits were computed
+                } else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {    // clamped rows are loaded but not used
-                        const int t = min(max(tt + (half * 4 + j) * 4 + row, p.n_vq), p.length - 1);
-                        const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
-                        vr[j] = *reinterpret_cast<const Half8*>(p.v_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
-                    }
+                    for (int j = 0; j < 8; ++j) vr[j] = load_value_row(tt, j);
+                }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int tl = (half * 4 + j) * 4 + row;
-                        const bool use = tl >= n_vq_here && tt + tl < p.length;
-                        float v[8];
-                        unpack8(vr[j], v);
+                for (int j = 0; j < 8; ++j) {
+                    const int tl = j * 4 + (lane >> 4);
+                    const bool use = tl >= n_vq_here && tt + tl < p.length;
+                    float v[8];
+                    unpack8(vr[j], v);
 #pragma unroll
-                        for (int hh = 0; hh < REP; ++hh) {
-                            const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
+                    for (int hh = 0; hh < REP; ++hh) {
+                        const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, v[e], racc[hh][e]);
-                        }
+                        for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, v[e], racc[hh][e]);
                     }
                 }
             }
