@@ -21,8 +21,6 @@ COMMON_FLAGS = [
     "-fhip-fp32-correctly-rounded-divide-sqrt",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # matrix-core results stay in ordinary vector registers (no copies to/from the accumulator file)
-    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 PER_FILE_FLAGS = {
     # the quantiser's (x - z) / s must stay a subtract followed by a division

@@ -9,8 +9,8 @@
 // position factor 4^j and the group's scale go into the small operand:
 //   keys  : a_t = sum_c [code_tc 4^j] [q_c s_c 4^-j]     + sum_c q_c z_c        (per tile of 32 tokens)
 //   values: o_c = sum_t [code_tc 4^j] [p_t s_t,g 4^-j]   + sum_t p_t z_t,g
-// and the small operand is split into fp16 hi + lo parts in two matrix columns, which restores
-// fp32-class accuracy.  The z-term of the keys is itself a 16x16x32 product (zero-points are
+// and the small operand is split into fp16 hi + (magnified) lo parts in two matrix columns, which
+// restores fp32-class accuracy.  The z-term of the keys is itself a 16x16x32 product (zero-points are
 // exact fp16).  The fp16 residual rows are 5x the bytes per element, so they stay on the vector
 // ALUs.
 //
@@ -144,10 +144,15 @@ __device__ __forceinline__ half8 code_fragment(const uint32_t* w, int pair, int 
     return f.h;
 }
 
+// x = hi + lo * 2^-11 with hi = fp16(x).  The remainder is stored magnified by 2^11: it stays a
+// normal fp16 number wherever hi is one, and when x is so small that hi is subnormal (products
+// with tiny softmax probabilities) it still adds 11 bits below fp16's subnormal spacing.
+constexpr float kLoMagnify = 2048.0f, kLoShrink = 1.0f / 2048.0f;
 __device__ __forceinline__ void split_hi_lo(float x, __half& hi, __half& lo) {
     hi = __float2half_rn(x);
-    lo = __float2half_rn(x - __half2float(hi));
+    lo = __float2half_rn((x - __half2float(hi)) * kLoMagnify);
 }
+__device__ __forceinline__ float join_hi_lo(float hi, float lo) { return fmaf(lo, kLoShrink, hi); }
 
 // LDS of one wavefront.  `lr` holds, per matrix column (head, hi/lo), the raw matrix-core logits
 // of the wave's 128 token slots; after the softmax the hi column of a head holds its
@@ -390,7 +395,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
                 const float mw = sm_ml[wv][hh][0];
                 if (mw > -INFINITY) {
                     const float wgt = __expf(mw - m);
-                    const float ow = fmaf(sm_w[wv].lr[2 * hh][c] + sm_w[wv].lr[2 * hh + 1][c], kUnscale,
+                    const float ow = fmaf(join_hi_lo(sm_w[wv].lr[2 * hh][c], sm_w[wv].lr[2 * hh + 1][c]), kUnscale,
                                           sm_zs[wv][hh][c >> 5]) + sm_r[wv][hh][c];
                     l = fmaf(sm_ml[wv][hh][1], wgt, l);
                     o = fmaf(ow, wgt, o);
@@ -475,9 +480,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
             for (int hh = 0; hh < REP; ++hh) {
                 const float2 hi = *reinterpret_cast<const float2*>(&wl.lr[2 * hh][2 * lane]);
                 const float2 lo = *reinterpret_cast<const float2*>(&wl.lr[2 * hh + 1][2 * lane]);
-                const float zt = wl.zt[2 * hh][slot] + wl.zt[2 * hh + 1][slot];
-                a0[hh] = live ? fmaf(hi.x + lo.x, kUnscale, zt) : -INFINITY;
-                a1[hh] = live ? fmaf(hi.y + lo.y, kUnscale, zt) : -INFINITY;
+                const float zt = join_hi_lo(wl.zt[2 * hh][slot], wl.zt[2 * hh + 1][slot]);
+                a0[hh] = live ? fmaf(join_hi_lo(hi.x, lo.x), kUnscale, zt) : -INFINITY;
+                a1[hh] = live ? fmaf(join_hi_lo(hi.y, lo.y), kUnscale, zt) : -INFINITY;
                 const float mx = wave_max(fmaxf(a0[hh], a1[hh]));
                 if (mx > m_run[hh]) {                       // wave-uniform: the running maximum grows
                     const float f = __expf(m_run[hh] - mx); // 0 on the first chunk (m_run = -inf)

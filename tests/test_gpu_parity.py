@@ -146,3 +146,25 @@ def test_run_twice_is_deterministic(path):
     a = gh.gpu_attention(layout, cache, q, w.softmax_scale)
     b = gh.gpu_attention(layout, cache, q, w.softmax_scale)
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("bits", [2, 4])
+def test_probability_accuracy_with_one_hot_values(path, bits):
+    """Tighter than the gate: with one-hot value rows the output is the softmax probability of
+    each token, so a lost low-order part of the small matrix operand (an error of ~2e-4 in a
+    probability) shows up directly.  Probabilities above 1e-3 must be within 5e-5 relative."""
+    torch = gh.require_gpu()
+    w = scaled(CONFIGS["llama7b"], name="onehot", batch=1, n_q_heads=1, n_kv_heads=1, bits=bits, residual=0, seed=5)
+    L = 128
+    k = workloads.keys(w, L)
+    q = (workloads.queries(w).astype(np.float32) * 0.25).astype(np.float16)
+    v = np.zeros((1, 1, L, 128), np.float16)
+    v[0, 0, np.arange(L), np.arange(L)] = 1.0
+    layout, cache = gh.gpu_prefill(w, k, v, kivi.KIVI_FLUSH_WINDOW, path)
+    oc = gh.oracle_cache_for_heads(w, k, v, [(0, 0)], "window")
+    out = gh.gpu_attention(layout, cache, q, w.softmax_scale)[0, 0].astype(np.float64)
+    ref = gh.oracle_attention_for_heads(w, oc, q, [(0, 0)])[0, 0]
+    big = ref > 1e-3
+    assert big.sum() > 50
+    assert np.abs(out[big] / ref[big] - 1).max() < 5e-5
