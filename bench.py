@@ -28,7 +28,11 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per decode-attention launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by the factor a plain copy kernel of known size reads on the same counters; see the
 # summaries under profiles/.  None until measured for a workload/path.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/decode_mfma_llama7b.md: FETCH_SIZE 112237.3 KiB x 2.0 + WRITE_SIZE 880.0 KiB x 1.0
+    ("llama7b", "mfma"): 112237.3 * 1024 * 2.0 + 880.0 * 1024,
+    ("llama7b", "auto"): 112237.3 * 1024 * 2.0 + 880.0 * 1024,
+}
 
 
 def parse_args():
@@ -40,6 +44,8 @@ def parse_args():
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--copies", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -119,37 +125,46 @@ def main():
     v_new = vt[:, :, L - 1].contiguous()
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
 
-    def step(c, ev_a=None, ev_b=None):
+    def step(c):
         # the newest token is (re-)appended as the last residual token, then flush check, then attention
         c.c.n_kr -= 1
         c.c.n_vr -= 1
         kivi.kivi_append_residual(layout, c, k_new, v_new, stream)
         kivi.kivi_flush_residual(layout, c, kivi.KIVI_FLUSH_WINDOW, stream)
-        if ev_a is not None:
-            ev_a.record(stream)
         kivi.kivi_decode_attention(layout, c, qt, w.softmax_scale, out, stream)
-        if ev_b is not None:
-            ev_b.record(stream)
 
-    def timed(n_steps, rotate):
-        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_steps)]
+    def timed(n_steps, rotate, attention_only):
+        """Average GPU time per iteration between two events on the launch stream."""
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record(stream)
         for i in range(n_steps):
-            step(caches[i % len(caches)] if rotate else caches[0], *pairs[i])
+            c = caches[i % len(caches)] if rotate else caches[0]
+            if attention_only:
+                kivi.kivi_decode_attention(layout, c, qt, w.softmax_scale, out, stream)
+            else:
+                step(c)
         ev1.record(stream)
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
-        gpu_ms = ev0.elapsed_time(ev1)
-        attn_ms = sum(a.elapsed_time(b) for a, b in pairs) / n_steps
-        return gpu_ms / n_steps, attn_ms, wall_ms / n_steps
+        return ev0.elapsed_time(ev1) / n_steps, wall_ms / n_steps
 
     for i in range(args.warmup):
         step(caches[i % len(caches)])
     torch.cuda.synchronize()
-    cold_step_ms, cold_attn_ms, cold_wall_ms = timed(args.steps, rotate=True)
-    warm_step_ms, warm_attn_ms, _ = timed(args.steps, rotate=False)
+    cold_step_ms, cold_wall_ms = timed(args.steps, rotate=True, attention_only=False)
+    warm_step_ms, _ = timed(args.steps, rotate=False, attention_only=False)
+    # the dominant kernel alone: back-to-back decode-attention launches (one kernel per launch in the
+    # matrix-core family), cold = rotating over the cache copies
+    cold_attn_ms, _ = timed(args.steps, rotate=True, attention_only=True)
+    warm_attn_ms, _ = timed(args.steps, rotate=False, attention_only=True)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     bytes_ = w.algorithmic_bytes(n_q, n_r)
     achieved = bytes_["all"] / (cold_attn_ms * 1e-3) / 1e9
@@ -171,7 +186,7 @@ def main():
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC.get((w.name, args.path)),
-            "kernel": "kivi_decode_attention (split kernel + merge), HIP events on the launch stream, cold cache copies",
+            "kernel": "kivi_decode_attention: back-to-back launches between two HIP events on the launch stream, rotating cache copies (cold)",
             "algorithmic_bytes_per_launch": bytes_["all"],
             "achieved_packed_only": achieved_packed,
             "frac_packed_only": achieved_packed / HBM_PEAK_GBS,

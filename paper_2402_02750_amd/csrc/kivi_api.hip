@@ -192,17 +192,14 @@ int kivi_append_residual(const kivi_layout_t* l, kivi_cache_t* c, const void* k_
     if (int s = check_cache(l, c)) return s;
     if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return KIVI_ERR_INVALID_ARG;
     if (c->n_kr >= l->cap_r_tokens || c->n_vr >= l->cap_r_tokens) return KIVI_ERR_INVALID_ARG;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
     const int64_t sh = kHeadDim, sb = sh * l->n_kv_heads;
     CopyRowsParams p{};
-    p.stride_b = sb; p.stride_h = sh; p.stride_t = kHeadDim; p.src_t0 = 0;
-    p.cap_r = l->cap_r_tokens; p.n_tokens = 1; p.n_kv_heads = l->n_kv_heads; p.batch = l->batch;
-    p.src = static_cast<const __half*>(k_new); p.dst = static_cast<__half*>(c->k_resid);
-    p.dst_slot0 = (c->k_r_start + c->n_kr) % l->cap_r_tokens;
-    if (int s = hip_status(launch_copy_rows(p, hs))) return s;
-    p.src = static_cast<const __half*>(v_new); p.dst = static_cast<__half*>(c->v_resid);
-    p.dst_slot0 = (c->v_r_start + c->n_vr) % l->cap_r_tokens;
-    if (int s = hip_status(launch_copy_rows(p, hs))) return s;
+    p.cap_r = l->cap_r_tokens; p.n_kv_heads = l->n_kv_heads; p.batch = l->batch;
+    p.job[0] = {static_cast<const __half*>(k_new), sb, sh, kHeadDim, 0, static_cast<__half*>(c->k_resid),
+                (c->k_r_start + c->n_kr) % l->cap_r_tokens, 1};
+    p.job[1] = {static_cast<const __half*>(v_new), sb, sh, kHeadDim, 0, static_cast<__half*>(c->v_resid),
+                (c->v_r_start + c->n_vr) % l->cap_r_tokens, 1};
+    if (int s = hip_status(launch_copy_rows(p, static_cast<hipStream_t>(stream)))) return s;
     c->n_kr += 1;
     c->n_vr += 1;
     return KIVI_OK;
@@ -272,12 +269,9 @@ int kivi_prefill(const kivi_layout_t* l, const void* k, int64_t ksb, int64_t ksh
         if (int s = enqueue_value_quant(l, c, src, nvq, hs)) return s;
     }
     CopyRowsParams p{};
-    p.cap_r = l->cap_r_tokens; p.n_kv_heads = l->n_kv_heads; p.batch = l->batch; p.dst_slot0 = 0;
-    p.src = static_cast<const __half*>(k); p.stride_b = ksb; p.stride_h = ksh; p.stride_t = kst;
-    p.src_t0 = nkq; p.n_tokens = nkr; p.dst = static_cast<__half*>(c->k_resid);
-    if (int s = hip_status(launch_copy_rows(p, hs))) return s;
-    p.src = static_cast<const __half*>(v); p.stride_b = vsb; p.stride_h = vsh; p.stride_t = vst;
-    p.src_t0 = nvq; p.n_tokens = nvr; p.dst = static_cast<__half*>(c->v_resid);
+    p.cap_r = l->cap_r_tokens; p.n_kv_heads = l->n_kv_heads; p.batch = l->batch;
+    p.job[0] = {static_cast<const __half*>(k), ksb, ksh, kst, nkq, static_cast<__half*>(c->k_resid), 0, nkr};
+    p.job[1] = {static_cast<const __half*>(v), vsb, vsh, vst, nvq, static_cast<__half*>(c->v_resid), 0, nvr};
     if (int s = hip_status(launch_copy_rows(p, hs))) return s;
     c->n_kq = nkq; c->n_vq = nvq; c->n_kr = nkr; c->n_vr = nvr; c->k_r_start = 0; c->v_r_start = 0;
     return KIVI_OK;

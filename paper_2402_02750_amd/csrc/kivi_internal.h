@@ -46,14 +46,18 @@ struct QuantValueParams {
     int32_t batch;
 };
 
-// Copy fp16 rows of every (b, h) from a strided tensor into a residual ring.
+// Copy fp16 rows of every (b, h) from strided tensors into residual rings: up to two (source,
+// ring) pairs per launch (keys and values), the second is skipped when its n_tokens is 0.
 struct CopyRowsParams {
-    const __half* src;    // element (b, h, t, c) at src[b*stride_b + h*stride_h + (src_t0 + t)*stride_t + c]
-    int64_t stride_b, stride_h, stride_t;
-    int32_t src_t0;
-    __half* dst;          // [b][h][cap_r][128]
-    int32_t dst_slot0;    // row t goes to slot (dst_slot0 + t) % cap_r
-    int32_t cap_r, n_tokens, n_kv_heads, batch;
+    struct Job {
+        const __half* src;    // element (b, h, t, c) at src[b*stride_b + h*stride_h + (src_t0 + t)*stride_t + c]
+        int64_t stride_b, stride_h, stride_t;
+        int32_t src_t0;
+        __half* dst;          // [b][h][cap_r][128]
+        int32_t dst_slot0;    // row t goes to slot (dst_slot0 + t) % cap_r
+        int32_t n_tokens;
+    } job[2];
+    int32_t cap_r, n_kv_heads, batch;
 };
 
 // How the token axis [0, L) is cut into context splits (one workgroup each per (b, kv-head)).

@@ -169,15 +169,18 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
 }
 
 __global__ __launch_bounds__(256) void copy_rows_kernel(CopyRowsParams p) {
-    // one thread moves 16 bytes
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    // one thread moves 16 bytes; blockIdx.x covers job 0's rows, then job 1's
+    const int blocks0 = (p.job[0].n_tokens * 16 + 255) / 256;
+    const int which = (int)blockIdx.x >= blocks0 ? 1 : 0;
+    const CopyRowsParams::Job& j = p.job[which];
+    const int i = ((int)blockIdx.x - (which ? blocks0 : 0)) * 256 + (int)threadIdx.x;
     const int h = blockIdx.y, b = blockIdx.z;
-    if (i >= p.n_tokens * 16) return;
+    if (i >= j.n_tokens * 16) return;
     const int t = i >> 4, seg = i & 15;
-    const __half* src = p.src + (int64_t)b * p.stride_b + (int64_t)h * p.stride_h
-                        + (int64_t)(p.src_t0 + t) * p.stride_t + seg * 8;
-    const int slot = (p.dst_slot0 + t) % p.cap_r;
-    __half* dst = p.dst + (((int64_t)b * p.n_kv_heads + h) * p.cap_r + slot) * kHeadDim + seg * 8;
+    const __half* src = j.src + (int64_t)b * j.stride_b + (int64_t)h * j.stride_h
+                        + (int64_t)(j.src_t0 + t) * j.stride_t + seg * 8;
+    const int slot = (j.dst_slot0 + t) % p.cap_r;
+    __half* dst = j.dst + (((int64_t)b * p.n_kv_heads + h) * p.cap_r + slot) * kHeadDim + seg * 8;
     *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
 }
 
@@ -202,8 +205,9 @@ hipError_t launch_quantize_values(const QuantValueParams& p, hipStream_t stream)
 }
 
 hipError_t launch_copy_rows(const CopyRowsParams& p, hipStream_t stream) {
-    if (p.n_tokens <= 0) return hipSuccess;
-    dim3 grid((p.n_tokens * 16 + 255) / 256, p.n_kv_heads, p.batch), block(256);
+    const int blocks = (p.job[0].n_tokens * 16 + 255) / 256 + (p.job[1].n_tokens * 16 + 255) / 256;
+    if (blocks <= 0) return hipSuccess;
+    dim3 grid(blocks, p.n_kv_heads, p.batch), block(256);
     copy_rows_kernel<<<grid, block, 0, stream>>>(p);
     return hipGetLastError();
 }
