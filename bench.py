@@ -43,6 +43,7 @@ def parse_args():
     ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "llama13b_4bit", "mistral_gqa"])
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--copies", type=int, default=5)
+    ap.add_argument("--context", type=int, default=0, help="override the workload's context length (scaling studies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -95,6 +96,8 @@ def main():
     kivi.load_library()
     torch.cuda.set_device(0)
     w = workloads.CONFIGS[args.workload]
+    if args.context:
+        w = workloads.scaled(w, name=f"{w.name}@{args.context}", context=args.context)
     n_q, n_r = w.split_single_step()
     L = w.context
     path = {"auto": kivi.KIVI_DECODE_AUTO, "valu": kivi.KIVI_DECODE_VALU, "mfma": kivi.KIVI_DECODE_MFMA}[args.path]

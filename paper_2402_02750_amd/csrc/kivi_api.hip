@@ -76,6 +76,9 @@ SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, int max_til
     int tps = (int)std::min<int64_t>(max_tiles, ((int64_t)s.tiles_a * units + target_wgs - 1) / target_wgs);
     tps = std::max(tps, std::min(max_tiles, 4 * rep));
     s.tiles_per_split_a = std::max(1, std::min(tps, max_tiles));
+    // The persistent matrix-core kernel always walks full 16-tile chunks (4 slots per wavefront):
+    // shorter chunks would only re-read masked tiles.
+    if (max_tiles == kMfmaSplitTiles) s.tiles_per_split_a = kMfmaSplitTiles;
     // fp16 rows cost 512 B per token against 96 B (2-bit) or 160 B (4-bit)
     const int packed_per_tile = kTileTokens * 2 * (kHeadDim * l->bits / 8 + 16);
     const int fp16_per_tile = kTileTokens * 2 * kHeadDim * 2;

@@ -108,6 +108,15 @@ __device__ __forceinline__ float device_load(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// fp16 x fp16 dot product of 8 elements with fp32 accumulation (v_dot2_f32_f16)
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot8(half8 a, half8 b) {
+    float r = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), 0.f, false);
+    r = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), r, false);
+    r = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), r, false);
+    return __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), r, false);
+}
+
 __device__ __forceinline__ float pow2_neg(int e) {   // 2^-e, 0 <= e < 64
     return __int_as_float((127 - e) << 23);
 }
@@ -246,7 +255,7 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
 }
 
 template <int BITS, int REP>
-__global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
+__global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
     using WL = WaveLds<REP>;
     constexpr int NC = 2 * REP;                       // live matrix columns: (head, hi/lo)
     constexpr int SS = WL::kStageSlots;
@@ -296,37 +305,23 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
         nx_base = (int64_t)nx_u * p.cap_tiles + tile0;
     };
     auto chunk_tile = [&](int slot_or_row) -> int64_t { return nx_base + min(wave + 4 * slot_or_row, nx_nt - 1); };
-    // requests for all-quantised chunk ck; one past this workgroup's range clears the registers instead
+    // Requests for the "next" all-quantised chunk.  They are issued unconditionally so that the
+    // compiler can count outstanding loads exactly (a conditional load forces a wait for *all*
+    // outstanding loads at the next use); when there is no next chunk they read tile 0 of unit 0,
+    // which stays in L2, and the result is never used.
     auto request_zero_rows = [&]() {
-        if (!nx_ok) {
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
-            return;
-        }
-        const int64_t tile = nx_base + min(wave + 4 * min(n, kSlots - 1), nx_nt - 1);   // A row n = slot n
+        const int64_t tile = nx_ok ? nx_base + min(wave + 4 * min(n, kSlots - 1), nx_nt - 1) : 0;   // A row n = slot n
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
             zf[ks] = *reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8);
     };
     auto request_key_slot = [&](int i) {
-        if (!nx_ok) {
-#pragma unroll
-            for (int k = 0; k < kLaneWords; ++k) kw[i][k] = 0u;
-            ks2[i] = __half2{};
-            return;
-        }
-        const int64_t tile = chunk_tile(i);
+        const int64_t tile = nx_ok ? chunk_tile(i) : 0;
         load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
         ks2[i] = *reinterpret_cast<const __half2*>(p.k_scale + tile * kHeadDim + 2 * lane);
     };
     auto request_value_slot = [&](int i) {
-        if (!nx_ok) {
-#pragma unroll
-            for (int k = 0; k < kLaneWords; ++k) vw[i][k] = 0u;
-            vs2[i] = vz2[i] = __half2{};
-            return;
-        }
-        const int64_t tile = chunk_tile(i);
+        const int64_t tile = nx_ok ? chunk_tile(i) : 0;
         load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
         vs2[i] = *reinterpret_cast<const __half2*>(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
         vz2[i] = *reinterpret_cast<const __half2*>(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
@@ -349,7 +344,7 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
     };
 
     // ---- leave a unit: merge the four wavefronts, write the output or this workgroup's part ----
-    auto finish_unit = [&](int u, bool in_loop_b) {
+    auto finish_unit = [&](int u) {
         const int hq0 = (u % p.n_kv_heads) * REP;
         const int b = u / p.n_kv_heads;
         // raw matrix-core outputs: column n of acc[u8] -> lr[n][channel]
@@ -375,14 +370,17 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
         }
         __syncthreads();
 
-        // workgroups contributing to unit u: those whose all-quantised range touches it, then those
-        // whose fp16-row range touches it
+        // Workgroups contributing to unit u: the union of those whose all-quantised range touches it
+        // and those whose fp16-row range touches it (each contributes one part).
+        const int g = blockIdx.x;
         const int ga0 = n_a ? (u * n_a) / p.chunks_per_wg_a : 0;
-        const int parts_a = n_a ? ((u + 1) * n_a - 1) / p.chunks_per_wg_a - ga0 + 1 : 0;
+        const int len_a = n_a ? ((u + 1) * n_a - 1) / p.chunks_per_wg_a - ga0 + 1 : 0;
         const int gb0 = n_b ? (u * n_b) / p.chunks_per_wg_b : 0;
-        const int parts_b = n_b ? ((u + 1) * n_b - 1) / p.chunks_per_wg_b - gb0 + 1 : 0;
-        const int n_parts = parts_a + parts_b;
-        const int part = in_loop_b ? parts_a + (int)blockIdx.x - gb0 : (int)blockIdx.x - ga0;
+        const int len_b = n_b ? ((u + 1) * n_b - 1) / p.chunks_per_wg_b - gb0 + 1 : 0;
+        const int o0 = max(ga0, gb0);
+        const int overlap = (len_a && len_b) ? max(0, min(ga0 + len_a, gb0 + len_b) - o0) : 0;
+        const int n_parts = len_a + len_b - overlap;
+        const int part = min(max(g - ga0, 0), len_a) + min(max(g - gb0, 0), len_b) - min(max(g - o0, 0), overlap);
         const int row_stride = cpu;                               // workspace rows per (batch, query head)
         for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
             const int hh = idx / kHeadDim, c = idx % kHeadDim;
@@ -512,26 +510,187 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
 
     };
 
-    int cur_unit = -1;
-
-    // ================= loop 1: all-quantised chunks, software-pipelined =================
-    if (first_a < last_a) {
+    // ================= main loop: the units this workgroup touches, in order =================
+    // For each unit: first its chunks with fp16 rows (they load their own rows; the request for the
+    // unit's first all-quantised chunk is already in flight, so the two latencies overlap), then its
+    // all-quantised chunks inside this workgroup's range (software-pipelined); one running state for
+    // both, then finish_unit.
+    const int u_lo = min(first_a < last_a ? first_a / max(n_a, 1) : 0x7fffffff,
+                         first_b < last_b ? first_b / max(n_b, 1) : 0x7fffffff);
+    const int u_hi = max(first_a < last_a ? (last_a - 1) / max(n_a, 1) : -1,
+                         first_b < last_b ? (last_b - 1) / max(n_b, 1) : -1);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
+    for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
+    if (first_a < last_a) {
         set_next(first_a, true);
         request_zero_rows();
 #pragma unroll
         for (int i = 0; i < kSlots; ++i) request_key_slot(i);
 #pragma unroll
         for (int i = 0; i < kSlots; ++i) request_value_slot(i);
-        for (int ck = first_a; ck < last_a; ++ck) {
-            const int u = nx_u, n_tiles = nx_nt;         // the chunk requested last is the one processed now
-            set_next(ck + 1, false);
-            if (u != cur_unit) {
-                if (cur_unit >= 0) finish_unit(cur_unit, false);
-                enter_unit(u);
-                cur_unit = u;
+    }
+    for (int u = u_lo; u <= u_hi; ++u) {
+        const int a_lo = max(first_a, u * n_a), a_hi = min(last_a, (u + 1) * n_a);
+        const int b_lo = max(first_b, u * n_b), b_hi = min(last_b, (u + 1) * n_b);
+        if (a_lo >= a_hi && b_lo >= b_hi) continue;
+        enter_unit(u);
+
+        // ---------- chunks that hold fp16 rows ----------
+        for (int ck = b_lo; ck < b_hi; ++ck) {
+            const int tile0 = p.plan.tiles_a + (ck - u * n_b) * p.plan.tiles_per_split_b;
+            const int n_tiles = min(p.plan.tiles_per_split_b, p.plan.tiles_total - tile0);
+            const int64_t unit = u;
+            const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
+            const int64_t ubase = unit * p.cap_tiles + tile0;
+            if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
+            // how many of the wave's tiles are quantised key tiles (they come first in token order)
+            int cnt_kq = 0;
+            for (int i = 0; i < cnt; ++i) cnt_kq += ((tile0 + wave + 4 * i) * kTileTokens < p.n_kq) ? 1 : 0;
+            if (cnt_kq > 0) {
+                const __half* zrow = p.k_zero + (ubase + wave + 4 * min(n, cnt_kq - 1)) * kHeadDim;
+                float4v d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const half8 za = *reinterpret_cast<const half8*>(zrow + ks * 32 + rq * 8);
+                    const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[ncol][ks * 32 + rq * 8]);
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(za, bq, d, 0, 0, 0);
+                }
+                wave_lds_sync();
+                if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
             }
+            // fp16 value rows of the wave's first tile are requested now, ahead of the logits
+            // lane (seg, row): row j*4 + (lane >> 4) of the tile, channels (lane & 15)*8 ..; clamped rows are not used
+            auto load_value_row = [&](int tt, int j) -> half8 {
+                const int t = min(max(tt + j * 4 + (lane >> 4), p.n_vq), p.length - 1);
+                const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
+                return *reinterpret_cast<const half8*>(p.v_resid + (unit * p.cap_r + slot) * kHeadDim + (lane & 15) * 8);
+            };
+            half8 vr0[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) vr0[j] = half8{};
+            if (cnt > 0 && p.n_vr > 0 && p.n_vq < (tile0 + wave + 1) * kTileTokens) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) vr0[j] = load_value_row((tile0 + wave) * kTileTokens, j);
+            }
+            // ---- phase 1: raw logits ----
+            for (int i = 0; i < cnt; ++i) {
+                const int tile = tile0 + wave + 4 * i;
+                const int tt = tile * kTileTokens;
+                if (tt < p.n_kq) {
+                    uint32_t w[kLaneWords];
+                    load_tile_words<BITS>(p.k_codes + (ubase + wave + 4 * i) * kWords, lane, w);
+                    const __half2 s2 = *reinterpret_cast<const __half2*>(
+                        p.k_scale + (ubase + wave + 4 * i) * kHeadDim + 2 * lane);
+                    stage_key_operand<REP>(wl.b, s2, qpf, lane);
+                    wave_lds_sync();
+                    key_tile_mfma<BITS, REP>(w, wl.b, wl.lr, i, lane);
+                    wave_lds_sync();
+                } else {
+                    // fp16 residual keys on the vector ALUs: lane (seg, row) takes channels seg*8.. of rows
+                    // row, row+4, ...; fp16 x fp16 dot products (v_dot2) with fp32 accumulation.  The
+                    // finished logit a is stored as a * 2^-24 in the head's hi column (lo column and
+                    // z-term 0), which the softmax turns back into a exactly.
+                    const int seg = lane & 15, row = lane >> 4;
+                    half8 kr[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {    // every row load of the tile first; rows past the end re-read the last row
+                        const int t = min(tt + j * 4 + row, p.length - 1);
+                        const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
+                        kr[j] = *reinterpret_cast<const half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
+                    }
+                    const int64_t qrow = ((int64_t)(u / p.n_kv_heads) * p.n_q_heads + (u % p.n_kv_heads) * REP) * kHeadDim;
+#pragma unroll
+                    for (int hh = 0; hh < REP; ++hh) {
+                        const half8 qh = *reinterpret_cast<const half8*>(p.q + qrow + hh * kHeadDim + seg * 8);
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int tl = j * 4 + row;
+                            float a = dot8(kr[j], qh);
+                            a += dpp<kDppXor1>(a); a += dpp<kDppXor2>(a);
+                            a += dpp<kDppHalfMirror>(a); a += dpp<kDppMirror>(a);
+                            if (seg == 0) {
+                                wl.lr[2 * hh][i * kTileTokens + tl] =
+                                    tt + tl < p.length ? a * (p.softmax_scale * kDownscale) : -INFINITY;
+                                wl.lr[2 * hh + 1][i * kTileTokens + tl] = 0.f;
+                            }
+                        }
+                    }
+                }
+            }
+            wave_lds_sync();
+            softmax_step(cnt);
+            wave_lds_sync();
+            // ---- phase 3: outputs ----
+            {
+                float racc[REP][8];
+#pragma unroll
+            for (int hh = 0; hh < REP; ++hh)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) racc[hh][e] = 0.f;
+            for (int i = 0; i < cnt; ++i) {
+                const int tile = tile0 + wave + 4 * i;
+                const int tt = tile * kTileTokens;
+                const int n_vq_here = min(max(p.n_vq - tt, 0), kTileTokens);
+                if (n_vq_here > 0) {
+                    uint32_t w[kLaneWords];
+                    load_tile_words<BITS>(p.v_codes + (ubase + wave + 4 * i) * kWords, lane, w);
+                    const int64_t so = (ubase + wave + 4 * i) * kTileTokens * 4 + 2 * lane;
+                    const __half2 s2 = *reinterpret_cast<const __half2*>(p.v_scale + so);
+                    const __half2 z2 = *reinterpret_cast<const __half2*>(p.v_zero + so);
+                    stage_value_operand<BITS, REP>(wl.b, s2, z2, n_vq_here, wl.lr, i, zacc, lane);
+                    wave_lds_sync();
+                    value_tile_mfma<BITS, REP>(w, wl.b, acc, lane);
+                    wave_lds_sync();
+                }
+                if (n_vq_here < kTileTokens && p.n_vr > 0) {
+                    // fp16 residual values on the vector ALUs: lane (seg, row)
+                    half8 vr[8];
+                    if (i == 0) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) vr[j] = vr0[j];      // requested before the logits were computed
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) vr[j] = load_value_row(tt, j);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int tl = j * 4 + (lane >> 4);
+                        const bool use = tl >= n_vq_here && tt + tl < p.length;
+#pragma unroll
+                        for (int hh = 0; hh < REP; ++hh) {
+                            const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, (float)vr[j][e], racc[hh][e]);
+                        }
+                    }
+                }
+            }
+            // lane (seg, row) holds channels seg*8.. of every 4th row: add the four row groups into LDS
+            wave_lds_sync();
+#pragma unroll
+            for (int hh = 0; hh < REP; ++hh) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float rr = racc[hh][e];
+                    rr += __shfl_xor(rr, 16); rr += __shfl_xor(rr, 32);
+                    racc[hh][e] = rr;
+                }
+                if (lane < 16) {
+                    float* dst = &sm_r[wave][hh][lane * 8];
+                    float4 a = *reinterpret_cast<float4*>(dst), c = *reinterpret_cast<float4*>(dst + 4);
+                    a.x += racc[hh][0]; a.y += racc[hh][1]; a.z += racc[hh][2]; a.w += racc[hh][3];
+                    c.x += racc[hh][4]; c.y += racc[hh][5]; c.z += racc[hh][6]; c.w += racc[hh][7];
+                    *reinterpret_cast<float4*>(dst) = a;
+                    *reinterpret_cast<float4*>(dst + 4) = c;
+                }
+            }
+            }
+            wave_lds_sync();
+        }
+        // ---------- all-quantised chunks ----------
+        for (int ck = a_lo; ck < a_hi; ++ck) {
+            const int n_tiles = nx_nt;                   // the chunk requested last is the one processed now
+            set_next(ck + 1, false);
             const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;     // valid slots of this wavefront
             // key z-terms of the wave's four slots: one 16x16x128 product
             {
@@ -579,177 +738,9 @@ __global__ __launch_bounds__(256) void decode_mfma_kernel(DecodeParams p) {
             }
             wave_lds_sync();
         }
-        finish_unit(cur_unit, false);
-        cur_unit = -1;
-    }
 
-    // ================= loop 2: chunks that hold fp16 rows (each loads its own data) =================
-    for (int ck = first_b; ck < last_b; ++ck) {
-        const int u = ck / n_b;
-        const int tile0 = p.plan.tiles_a + (ck - u * n_b) * p.plan.tiles_per_split_b;
-        const int n_tiles = min(p.plan.tiles_per_split_b, p.plan.tiles_total - tile0);
-        if (u != cur_unit) {
-            if (cur_unit >= 0) finish_unit(cur_unit, true);
-            enter_unit(u);
-            cur_unit = u;
-        }
-        const int64_t unit = u;
-        const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
-        const int64_t ubase = unit * p.cap_tiles + tile0;
-        if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
-        // how many of the wave's tiles are quantised key tiles (they come first in token order)
-        int cnt_kq = 0;
-        for (int i = 0; i < cnt; ++i) cnt_kq += ((tile0 + wave + 4 * i) * kTileTokens < p.n_kq) ? 1 : 0;
-        if (cnt_kq > 0) {
-            const __half* zrow = p.k_zero + (ubase + wave + 4 * min(n, cnt_kq - 1)) * kHeadDim;
-            float4v d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                const half8 za = *reinterpret_cast<const half8*>(zrow + ks * 32 + rq * 8);
-                const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[ncol][ks * 32 + rq * 8]);
-                d = __builtin_amdgcn_mfma_f32_16x16x32_f16(za, bq, d, 0, 0, 0);
-            }
-            wave_lds_sync();
-            if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
-        }
-        // fp16 value rows of the wave's first tile are requested now, ahead of the logits
-        // lane (seg, row): row j*4 + (lane >> 4) of the tile, channels (lane & 15)*8 ..; clamped rows are not used
-        auto load_value_row = [&](int tt, int j) -> Half8 {
-            const int t = min(max(tt + j * 4 + (lane >> 4), p.n_vq), p.length - 1);
-            const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
-            return *reinterpret_cast<const Half8*>(p.v_resid + (unit * p.cap_r + slot) * kHeadDim + (lane & 15) * 8);
-        };
-        Half8 vr0[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) vr0[j] = Half8{};
-        if (cnt > 0 && p.n_vr > 0 && p.n_vq < (tile0 + wave + 1) * kTileTokens) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) vr0[j] = load_value_row((tile0 + wave) * kTileTokens, j);
-        }
-        // ---- phase 1: raw logits ----
-        for (int i = 0; i < cnt; ++i) {
-            const int tile = tile0 + wave + 4 * i;
-            const int tt = tile * kTileTokens;
-            if (tt < p.n_kq) {
-                uint32_t w[kLaneWords];
-                load_tile_words<BITS>(p.k_codes + (ubase + wave + 4 * i) * kWords, lane, w);
-                const __half2 s2 = *reinterpret_cast<const __half2*>(
-                    p.k_scale + (ubase + wave + 4 * i) * kHeadDim + 2 * lane);
-                stage_key_operand<REP>(wl.b, s2, qpf, lane);
-                wave_lds_sync();
-                key_tile_mfma<BITS, REP>(w, wl.b, wl.lr, i, lane);
-                wave_lds_sync();
-            } else {
-                // fp16 residual keys on the vector ALUs: lane (seg, row): 4 rows per step, 8 channels.
-                // The finished logit a is stored as a * 2^-24 in the head's hi column (lo column and
-                // z-term 0), which the softmax below turns back into a exactly.
-                const int seg = lane & 15, row = lane >> 4;
-                float qv[REP][8];
-#pragma unroll
-                for (int hh = 0; hh < REP; ++hh)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) qv[hh][e] = sm_q[hh][seg * 8 + e];
-                Half8 kr[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {        // every row load of the tile first; rows past the end re-read the last row
-                    const int t = min(tt + j * 4 + row, p.length - 1);
-                    const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
-                    kr[j] = *reinterpret_cast<const Half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int tl = j * 4 + row;
-                    const bool valid = tt + tl < p.length;
-                    float k[8];
-                    unpack8(kr[j], k);
-#pragma unroll
-                    for (int hh = 0; hh < REP; ++hh) {
-                        float a = 0.f;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) a = fmaf(qv[hh][e], k[e], a);
-                        a += dpp<kDppXor1>(a); a += dpp<kDppXor2>(a);
-                        a += dpp<kDppHalfMirror>(a); a += dpp<kDppMirror>(a);
-                        if (seg == 0) {
-                            wl.lr[2 * hh][i * kTileTokens + tl] = valid ? a * kDownscale : -INFINITY;
-                            wl.lr[2 * hh + 1][i * kTileTokens + tl] = 0.f;
-                        }
-                    }
-                }
-            }
-        }
-        wave_lds_sync();
-        softmax_step(cnt);
-        wave_lds_sync();
-        // ---- phase 3: outputs ----
-        {
-            float racc[REP][8];
-#pragma unroll
-        for (int hh = 0; hh < REP; ++hh)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) racc[hh][e] = 0.f;
-        for (int i = 0; i < cnt; ++i) {
-            const int tile = tile0 + wave + 4 * i;
-            const int tt = tile * kTileTokens;
-            const int n_vq_here = min(max(p.n_vq - tt, 0), kTileTokens);
-            if (n_vq_here > 0) {
-                uint32_t w[kLaneWords];
-                load_tile_words<BITS>(p.v_codes + (ubase + wave + 4 * i) * kWords, lane, w);
-                const int64_t so = (ubase + wave + 4 * i) * kTileTokens * 4 + 2 * lane;
-                const __half2 s2 = *reinterpret_cast<const __half2*>(p.v_scale + so);
-                const __half2 z2 = *reinterpret_cast<const __half2*>(p.v_zero + so);
-                stage_value_operand<BITS, REP>(wl.b, s2, z2, n_vq_here, wl.lr, i, zacc, lane);
-                wave_lds_sync();
-                value_tile_mfma<BITS, REP>(w, wl.b, acc, lane);
-                wave_lds_sync();
-            }
-            if (n_vq_here < kTileTokens && p.n_vr > 0) {
-                // fp16 residual values on the vector ALUs: lane (seg, row)
-                Half8 vr[8];
-                if (i == 0) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) vr[j] = vr0[j];      // requested before the logits were computed
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) vr[j] = load_value_row(tt, j);
-                }
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int tl = j * 4 + (lane >> 4);
-                    const bool use = tl >= n_vq_here && tt + tl < p.length;
-                    float v[8];
-                    unpack8(vr[j], v);
-#pragma unroll
-                    for (int hh = 0; hh < REP; ++hh) {
-                        const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, v[e], racc[hh][e]);
-                    }
-                }
-            }
-        }
-        // lane (seg, row) holds channels seg*8.. of every 4th row: add the four row groups into LDS
-        wave_lds_sync();
-#pragma unroll
-        for (int hh = 0; hh < REP; ++hh) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float rr = racc[hh][e];
-                rr += __shfl_xor(rr, 16); rr += __shfl_xor(rr, 32);
-                racc[hh][e] = rr;
-            }
-            if (lane < 16) {
-                float* dst = &sm_r[wave][hh][lane * 8];
-                float4 a = *reinterpret_cast<float4*>(dst), c = *reinterpret_cast<float4*>(dst + 4);
-                a.x += racc[hh][0]; a.y += racc[hh][1]; a.z += racc[hh][2]; a.w += racc[hh][3];
-                c.x += racc[hh][4]; c.y += racc[hh][5]; c.z += racc[hh][6]; c.w += racc[hh][7];
-                *reinterpret_cast<float4*>(dst) = a;
-                *reinterpret_cast<float4*>(dst + 4) = c;
-            }
-        }
-        }
-        wave_lds_sync();
+        finish_unit(u);
     }
-    if (cur_unit >= 0) finish_unit(cur_unit, true);
 }
 
 // Workgroups the chip holds at once for one instantiation (occupancy query, cached).
