@@ -68,6 +68,7 @@ __device__ __forceinline__ int ring_slot(int start, int i, int cap) {
 __device__ __forceinline__ void wave_lds_sync() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
 }
 
@@ -259,6 +260,10 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
     using WL = WaveLds<REP>;
     constexpr int NC = 2 * REP;                       // live matrix columns: (head, hi/lo)
     constexpr int SS = WL::kStageSlots;
+    // fp16-row chunks: rows held in registers at once, and whether the first tile's value rows are
+    // requested ahead of the logits (both cut for the wider instantiations: register pressure)
+    constexpr int RB = REP <= 2 ? 8 : 4;
+    constexpr bool kPreloadV = REP <= 2;
     __shared__ __align__(16) float sm_q[REP][kHeadDim];               // scale * q
     __shared__ __align__(16) __half sm_qf[NC][kKRow];                 // its hi/lo columns (z-term operand)
     __shared__ WL sm_w[4];
@@ -343,8 +348,16 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
         for (int i = lane; i < REP * kHeadDim; i += 64) (&sm_r[wave][0][0])[i] = 0.f;
     };
 
+    // workgroups whose all-quantised range / fp16-row range touches unit u: first index and count
+    auto contributors = [&](int u, int& ga0, int& len_a, int& gb0, int& len_b) {
+        ga0 = n_a ? (u * n_a) / p.chunks_per_wg_a : 0;
+        len_a = n_a ? ((u + 1) * n_a - 1) / p.chunks_per_wg_a - ga0 + 1 : 0;
+        gb0 = n_b ? (u * n_b) / p.chunks_per_wg_b : 0;
+        len_b = n_b ? ((u + 1) * n_b - 1) / p.chunks_per_wg_b - gb0 + 1 : 0;
+    };
+
     // ---- leave a unit: merge the four wavefronts, write the output or this workgroup's part ----
-    auto finish_unit = [&](int u) {
+    auto finish_unit = [&](int u, bool fp16_phase, bool sole) {
         const int hq0 = (u % p.n_kv_heads) * REP;
         const int b = u / p.n_kv_heads;
         // raw matrix-core outputs: column n of acc[u8] -> lr[n][channel]
@@ -370,17 +383,15 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
         }
         __syncthreads();
 
-        // Workgroups contributing to unit u: the union of those whose all-quantised range touches it
-        // and those whose fp16-row range touches it (each contributes one part).
+        // Parts of unit u: one per workgroup whose fp16-row range touches it (these come first), then
+        // one per workgroup whose all-quantised range touches it.
+        // (`sole`: this workgroup carried the unit's state from phase 1 into phase 2 and nobody
+        // else touches the unit -- a single part.)
         const int g = blockIdx.x;
-        const int ga0 = n_a ? (u * n_a) / p.chunks_per_wg_a : 0;
-        const int len_a = n_a ? ((u + 1) * n_a - 1) / p.chunks_per_wg_a - ga0 + 1 : 0;
-        const int gb0 = n_b ? (u * n_b) / p.chunks_per_wg_b : 0;
-        const int len_b = n_b ? ((u + 1) * n_b - 1) / p.chunks_per_wg_b - gb0 + 1 : 0;
-        const int o0 = max(ga0, gb0);
-        const int overlap = (len_a && len_b) ? max(0, min(ga0 + len_a, gb0 + len_b) - o0) : 0;
-        const int n_parts = len_a + len_b - overlap;
-        const int part = min(max(g - ga0, 0), len_a) + min(max(g - gb0, 0), len_b) - min(max(g - o0, 0), overlap);
+        int ga0, len_a, gb0, len_b;
+        contributors(u, ga0, len_a, gb0, len_b);
+        const int n_parts = sole ? 1 : len_a + len_b;
+        const int part = fp16_phase ? g - gb0 : len_b + g - ga0;
         const int row_stride = cpu;                               // workspace rows per (batch, query head)
         for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
             const int hh = idx / kHeadDim, c = idx % kHeadDim;
@@ -510,29 +521,26 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
 
     };
 
-    // ================= main loop: the units this workgroup touches, in order =================
-    // For each unit: first its chunks with fp16 rows (they load their own rows; the request for the
-    // unit's first all-quantised chunk is already in flight, so the two latencies overlap), then its
-    // all-quantised chunks inside this workgroup's range (software-pipelined); one running state for
-    // both, then finish_unit.
-    const int u_lo = min(first_a < last_a ? first_a / max(n_a, 1) : 0x7fffffff,
-                         first_b < last_b ? first_b / max(n_b, 1) : 0x7fffffff);
-    const int u_hi = max(first_a < last_a ? (last_a - 1) / max(n_a, 1) : -1,
-                         first_b < last_b ? (last_b - 1) / max(n_b, 1) : -1);
+    // ================= phase 1: this workgroup's chunks that hold fp16 rows =================
+    // They run before any all-quantised data is requested: the row loads, the vector-ALU
+    // accumulators and the registers of an in-flight quantised chunk do not fit side by side.
+    // Every unit touched here gets a part of its own (merged with the other parts of the unit by
+    // whichever workgroup finishes the unit last).
+    auto initial_request = [&]() {
+        if (first_a < last_a) {
+            set_next(first_a, true);
+            request_zero_rows();
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) zf[ks] = half8{};
-    if (first_a < last_a) {
-        set_next(first_a, true);
-        request_zero_rows();
+            for (int i = 0; i < kSlots; ++i) request_key_slot(i);
 #pragma unroll
-        for (int i = 0; i < kSlots; ++i) request_key_slot(i);
-#pragma unroll
-        for (int i = 0; i < kSlots; ++i) request_value_slot(i);
-    }
-    for (int u = u_lo; u <= u_hi; ++u) {
-        const int a_lo = max(first_a, u * n_a), a_hi = min(last_a, (u + 1) * n_a);
+            for (int i = 0; i < kSlots; ++i) request_value_slot(i);
+        }
+    };
+    const int ub_lo = first_b < last_b ? first_b / max(n_b, 1) : 0;
+    const int ub_hi = first_b < last_b ? (last_b - 1) / max(n_b, 1) : -1;
+    for (int u = ub_lo; u <= ub_hi; ++u) {
         const int b_lo = max(first_b, u * n_b), b_hi = min(last_b, (u + 1) * n_b);
-        if (a_lo >= a_hi && b_lo >= b_hi) continue;
+        if (u > ub_lo) finish_unit(u - 1, true, false);
         enter_unit(u);
 
         // ---------- chunks that hold fp16 rows ----------
@@ -565,12 +573,14 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
                 const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
                 return *reinterpret_cast<const half8*>(p.v_resid + (unit * p.cap_r + slot) * kHeadDim + (lane & 15) * 8);
             };
-            half8 vr0[8];
+            half8 vr0[kPreloadV ? 8 : 1];
+            if (kPreloadV) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) vr0[j] = half8{};
-            if (cnt > 0 && p.n_vr > 0 && p.n_vq < (tile0 + wave + 1) * kTileTokens) {
+                for (int j = 0; j < 8; ++j) vr0[j] = half8{};
+                if (cnt > 0 && p.n_vr > 0 && p.n_vq < (tile0 + wave + 1) * kTileTokens) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) vr0[j] = load_value_row((tile0 + wave) * kTileTokens, j);
+                    for (int j = 0; j < 8; ++j) vr0[j] = load_value_row((tile0 + wave) * kTileTokens, j);
+                }
             }
             // ---- phase 1: raw logits ----
             for (int i = 0; i < cnt; ++i) {
@@ -591,27 +601,30 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
                     // finished logit a is stored as a * 2^-24 in the head's hi column (lo column and
                     // z-term 0), which the softmax turns back into a exactly.
                     const int seg = lane & 15, row = lane >> 4;
-                    half8 kr[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {    // every row load of the tile first; rows past the end re-read the last row
-                        const int t = min(tt + j * 4 + row, p.length - 1);
-                        const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
-                        kr[j] = *reinterpret_cast<const half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
-                    }
                     const int64_t qrow = ((int64_t)(u / p.n_kv_heads) * p.n_q_heads + (u % p.n_kv_heads) * REP) * kHeadDim;
 #pragma unroll
-                    for (int hh = 0; hh < REP; ++hh) {
-                        const half8 qh = *reinterpret_cast<const half8*>(p.q + qrow + hh * kHeadDim + seg * 8);
+                    for (int j0 = 0; j0 < 8; j0 += RB) {
+                        half8 kr[RB];
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            const int tl = j * 4 + row;
-                            float a = dot8(kr[j], qh);
-                            a += dpp<kDppXor1>(a); a += dpp<kDppXor2>(a);
-                            a += dpp<kDppHalfMirror>(a); a += dpp<kDppMirror>(a);
-                            if (seg == 0) {
-                                wl.lr[2 * hh][i * kTileTokens + tl] =
-                                    tt + tl < p.length ? a * (p.softmax_scale * kDownscale) : -INFINITY;
-                                wl.lr[2 * hh + 1][i * kTileTokens + tl] = 0.f;
+                        for (int j = 0; j < RB; ++j) {   // the batch's row loads first; rows past the end re-read the last row
+                            const int t = min(tt + (j0 + j) * 4 + row, p.length - 1);
+                            const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
+                            kr[j] = *reinterpret_cast<const half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
+                        }
+#pragma unroll
+                        for (int hh = 0; hh < REP; ++hh) {
+                            const half8 qh = *reinterpret_cast<const half8*>(p.q + qrow + hh * kHeadDim + seg * 8);
+#pragma unroll
+                            for (int j = 0; j < RB; ++j) {
+                                const int tl = (j0 + j) * 4 + row;
+                                float a = dot8(kr[j], qh);
+                                a += dpp<kDppXor1>(a); a += dpp<kDppXor2>(a);
+                                a += dpp<kDppHalfMirror>(a); a += dpp<kDppMirror>(a);
+                                if (seg == 0) {
+                                    wl.lr[2 * hh][i * kTileTokens + tl] =
+                                        tt + tl < p.length ? a * (p.softmax_scale * kDownscale) : -INFINITY;
+                                    wl.lr[2 * hh + 1][i * kTileTokens + tl] = 0.f;
+                                }
                             }
                         }
                     }
@@ -644,23 +657,26 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
                 }
                 if (n_vq_here < kTileTokens && p.n_vr > 0) {
                     // fp16 residual values on the vector ALUs: lane (seg, row)
-                    half8 vr[8];
-                    if (i == 0) {
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) vr[j] = vr0[j];      // requested before the logits were computed
-                    } else {
+                    for (int j0 = 0; j0 < 8; j0 += RB) {
+                        half8 vr[RB];
+                        if (kPreloadV && i == 0) {
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) vr[j] = load_value_row(tt, j);
-                    }
+                            for (int j = 0; j < RB; ++j) vr[j] = vr0[j];     // requested before the logits were computed
+                        } else {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const int tl = j * 4 + (lane >> 4);
-                        const bool use = tl >= n_vq_here && tt + tl < p.length;
+                            for (int j = 0; j < RB; ++j) vr[j] = load_value_row(tt, j0 + j);
+                        }
 #pragma unroll
-                        for (int hh = 0; hh < REP; ++hh) {
-                            const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
+                        for (int j = 0; j < RB; ++j) {
+                            const int tl = (j0 + j) * 4 + (lane >> 4);
+                            const bool use = tl >= n_vq_here && tt + tl < p.length;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, (float)vr[j][e], racc[hh][e]);
+                            for (int hh = 0; hh < REP; ++hh) {
+                                const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, (float)vr[j][e], racc[hh][e]);
+                            }
                         }
                     }
                 }
@@ -687,7 +703,28 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
             }
             wave_lds_sync();
         }
-        // ---------- all-quantised chunks ----------
+    }
+
+    // ================= phase 2: this workgroup's all-quantised chunks =================
+    // Software-pipelined across chunk and unit borders: the next chunk's data is requested while
+    // the current one is consumed.
+    initial_request();                              // overlaps the merge of the last fp16-row unit
+    // If the last unit of phase 1 is the first unit of phase 2 and no other workgroup touches it, its
+    // running state simply carries over: no part, no merge.
+    bool carry = false;
+    const int ua_lo = first_a < last_a ? first_a / n_a : 0, ua_hi = first_a < last_a ? (last_a - 1) / n_a : -1;
+    if (ub_lo <= ub_hi) {
+        if (ua_lo <= ua_hi && ua_lo == ub_hi) {
+            int ga0, len_a, gb0, len_b;
+            contributors(ub_hi, ga0, len_a, gb0, len_b);
+            carry = len_a == 1 && len_b == 1;
+        }
+        if (!carry) finish_unit(ub_hi, true, false);
+    }
+    for (int u = ua_lo; u <= ua_hi; ++u) {
+        const int a_lo = max(first_a, u * n_a), a_hi = min(last_a, (u + 1) * n_a);
+        const bool carried = carry && u == ua_lo;
+        if (!carried) enter_unit(u);
         for (int ck = a_lo; ck < a_hi; ++ck) {
             const int n_tiles = nx_nt;                   // the chunk requested last is the one processed now
             set_next(ck + 1, false);
@@ -739,7 +776,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
             wave_lds_sync();
         }
 
-        finish_unit(u);
+        finish_unit(u, false, carried);
     }
 }
 
