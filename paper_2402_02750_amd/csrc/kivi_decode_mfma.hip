@@ -262,8 +262,8 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
     constexpr int SS = WL::kStageSlots;
     // fp16-row chunks: rows held in registers at once, and whether the first tile's value rows are
     // requested ahead of the logits (both cut for the wider instantiations: register pressure)
-    constexpr int RB = REP <= 2 ? 8 : 4;
-    constexpr bool kPreloadV = REP <= 2;
+    constexpr int RB = 8;
+    constexpr bool kPreloadV = true;
     __shared__ __align__(16) float sm_q[REP][kHeadDim];               // scale * q
     __shared__ __align__(16) __half sm_qf[NC][kKRow];                 // its hi/lo columns (z-term operand)
     __shared__ WL sm_w[4];
@@ -437,13 +437,28 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
                     const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
                     const float* ml = p.part_ml + row * row_stride * 2;
                     const float* po = p.part_o + row * row_stride * kHeadDim;
-                    float m = -INFINITY;
-                    for (int i = 0; i < n_parts; ++i) m = fmaxf(m, device_load(ml + 2 * i));
-                    float l = 0.f, o = 0.f;
-                    for (int i = 0; i < n_parts; ++i) {
-                        const float wgt = __expf(device_load(ml + 2 * i) - m);
-                        l = fmaf(device_load(ml + 2 * i + 1), wgt, l);
-                        o = fmaf(device_load(po + (int64_t)i * kHeadDim + c), wgt, o);
+                    // one pass, eight parts at a time: the device-scope loads of a batch are all
+                    // issued before the first is used (each is a trip to memory, not to a cache)
+                    float m = -INFINITY, l = 0.f, o = 0.f;
+                    for (int i0 = 0; i0 < n_parts; i0 += 8) {
+                        float mv[8], lv[8], ov[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int i = min(i0 + j, n_parts - 1);
+                            mv[j] = device_load(ml + 2 * i);
+                            lv[j] = device_load(ml + 2 * i + 1);
+                            ov[j] = device_load(po + (int64_t)i * kHeadDim + c);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            if (i0 + j < n_parts && mv[j] > -INFINITY) {
+                                const float mn = fmaxf(m, mv[j]);
+                                const float f_old = __expf(m - mn), f_new = __expf(mv[j] - mn);   // m = -inf: f_old = 0
+                                l = fmaf(l, f_old, lv[j] * f_new);
+                                o = fmaf(o, f_old, ov[j] * f_new);
+                                m = mn;
+                            }
+                        }
                     }
                     p.out[row * kHeadDim + c] = o / l;
                 }
