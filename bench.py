@@ -38,8 +38,9 @@ MEASURED_TRAFFIC = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500,
+                    help="untimed steps; a few hundred let the clocks settle (a step is ~50 us)")
     ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "llama13b_4bit", "mistral_gqa"])
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--copies", type=int, default=5)
@@ -129,12 +130,11 @@ def main():
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
 
     def step(c):
-        # the newest token is (re-)appended as the last residual token, then flush check, then attention
+        # one decoding step: the newest token is (re-)appended as the last residual token, the flush
+        # check runs, then attention -- kivi_decode_step does all three (one launch when no flush is due)
         c.c.n_kr -= 1
         c.c.n_vr -= 1
-        kivi.kivi_append_residual(layout, c, k_new, v_new, stream)
-        kivi.kivi_flush_residual(layout, c, kivi.KIVI_FLUSH_WINDOW, stream)
-        kivi.kivi_decode_attention(layout, c, qt, w.softmax_scale, out, stream)
+        kivi.kivi_decode_step(layout, c, k_new, v_new, qt, w.softmax_scale, out, kivi.KIVI_FLUSH_WINDOW, stream)
 
     def timed(n_steps, rotate, attention_only):
         """Average GPU time per iteration between two events on the launch stream."""
@@ -184,7 +184,7 @@ def main():
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads, "
                                f"head_dim 128, context {L} = {n_q} quantised ({w.bits}-bit, G=32) + {n_r} fp16 residual",
                    "decode_path": args.path, "cache_copies_rotated": len(caches),
-                   "step": "append newest token + flush check + decode attention"},
+                   "step": "kivi_decode_step: append newest token + flush check + decode attention"},
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,

@@ -127,6 +127,85 @@ int enqueue_value_quant(const kivi_layout_t* l, const kivi_cache_t* c, const Row
 
 using namespace kivi;
 
+namespace {
+
+// How many of the oldest residual tokens each policy moves into the quantised part (host logic).
+int plan_flush(const kivi_layout_t* l, const kivi_cache_t* c, int32_t policy, int* n_key, int* n_value) {
+    const int G = l->group, R = l->residual;
+    int nk = 0, nv = 0;
+    if (policy == KIVI_FLUSH_WINDOW) {
+        if (c->n_kr != c->n_vr || c->n_kq != c->n_vq) return KIVI_ERR_INVALID_ARG;   // symmetric policy
+        while (c->n_kr - nk >= R + G) nk += G;
+        nv = nk;
+    } else {
+        if (R > 0 && c->n_kr == R) nk = R;                 // Algorithm 1: len(X_Kr) == R
+        if (c->n_vr > R) nv = c->n_vr - R;                 // Algorithm 1: len(X_Vr) > R
+    }
+    if ((int64_t)c->n_kq + nk > l->cap_q_tokens || (int64_t)c->n_vq + nv > l->cap_q_tokens)
+        return KIVI_ERR_INVALID_ARG;
+    *n_key = nk;
+    *n_value = nv;
+    return KIVI_OK;
+}
+
+// Host checks shared by the two attention entry points (the cache counts are those the kernel will see).
+int check_attention_args(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, const float* out,
+                         const void* workspace, size_t workspace_bytes) {
+    if (!q || !out || !aligned16(q) || !aligned16(out)) return KIVI_ERR_INVALID_ARG;
+    const int length = c->n_kq + c->n_kr;
+    if (length < 1 || length != c->n_vq + c->n_vr) return KIVI_ERR_INVALID_ARG;
+    size_t need = 0;
+    kivi_decode_workspace_bytes(l, &need);
+    if (!workspace || !aligned16(workspace) || workspace_bytes < need) return KIVI_ERR_WORKSPACE;
+    return KIVI_OK;
+}
+
+int decode_family(const kivi_layout_t* l) {
+    // the matrix-core family covers up to 4 query heads per kv-head; 8 run on the vector ALUs
+    const int rep = l->n_q_heads / l->n_kv_heads;
+    return (l->decode_path == KIVI_DECODE_VALU || rep > 4) ? KIVI_DECODE_VALU : KIVI_DECODE_MFMA;
+}
+
+// Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the
+// rows of token length-1 are not in the rings yet and the (matrix-core) kernel puts them there.
+int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, float softmax_scale,
+                      float* out, void* workspace, const void* k_new, const void* v_new, void* stream) {
+    const int length = c->n_kq + c->n_kr;
+    DecodeParams p{};
+    p.k_codes = static_cast<const uint32_t*>(c->k_codes);
+    p.k_scale = static_cast<const __half*>(c->k_scale);
+    p.k_zero = static_cast<const __half*>(c->k_zero);
+    p.v_codes = static_cast<const uint32_t*>(c->v_codes);
+    p.v_scale = static_cast<const __half*>(c->v_scale);
+    p.v_zero = static_cast<const __half*>(c->v_zero);
+    p.k_resid = static_cast<const __half*>(c->k_resid);
+    p.v_resid = static_cast<const __half*>(c->v_resid);
+    p.n_kq = c->n_kq; p.n_vq = c->n_vq; p.k_r_start = c->k_r_start; p.n_kr = c->n_kr;
+    p.v_r_start = c->v_r_start; p.n_vr = c->n_vr;
+    p.cap_tiles = l->cap_q_tokens / kTileTokens; p.cap_r = l->cap_r_tokens;
+    p.q = static_cast<const __half*>(q); p.out = out;
+    p.softmax_scale = softmax_scale;
+    p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
+    p.length = length;
+    const int path = decode_family(l);
+    if ((k_new || v_new) && path != KIVI_DECODE_MFMA) return KIVI_ERR_UNSUPPORTED;
+    p.k_new = static_cast<const __half*>(k_new); p.v_new = static_cast<const __half*>(v_new);
+    p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA ? kMfmaSplitTiles : kMaxSplitTiles);
+    const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
+    p.counters = static_cast<int32_t*>(workspace);
+    p.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(l));
+    p.part_ml = p.part_o + rows * kHeadDim;
+
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipError_t e = path == KIVI_DECODE_MFMA ? launch_decode_mfma(p, hs) : launch_decode_valu(p, hs);
+    if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
+    if (int s = hip_status(e)) return s;
+    // the matrix-core kernel merges its splits itself; the vector-ALU family uses a second launch
+    return path == KIVI_DECODE_MFMA ? KIVI_OK : hip_status(launch_merge(p, hs));
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* kivi_status_string(int status) {
@@ -213,18 +292,8 @@ int kivi_flush_residual(const kivi_layout_t* l, kivi_cache_t* c, int32_t policy,
     if (int s = check_layout(l)) return s;
     if (int s = check_cache(l, c)) return s;
     if (policy != KIVI_FLUSH_WINDOW && policy != KIVI_FLUSH_ALG1) return KIVI_ERR_INVALID_ARG;
-    const int G = l->group, R = l->residual;
     int nk = 0, nv = 0;
-    if (policy == KIVI_FLUSH_WINDOW) {
-        if (c->n_kr != c->n_vr || c->n_kq != c->n_vq) return KIVI_ERR_INVALID_ARG;   // symmetric policy
-        while (c->n_kr - nk >= R + G) nk += G;
-        nv = nk;
-    } else {
-        if (R > 0 && c->n_kr == R) nk = R;                 // Algorithm 1: len(X_Kr) == R
-        if (c->n_vr > R) nv = c->n_vr - R;                 // Algorithm 1: len(X_Vr) > R
-    }
-    if ((int64_t)c->n_kq + nk > l->cap_q_tokens || (int64_t)c->n_vq + nv > l->cap_q_tokens)
-        return KIVI_ERR_INVALID_ARG;
+    if (int s = plan_flush(l, c, policy, &nk, &nv)) return s;
     const int64_t sh = (int64_t)l->cap_r_tokens * kHeadDim, sb = sh * l->n_kv_heads;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (nk > 0) {
@@ -284,44 +353,38 @@ int kivi_decode_attention(const kivi_layout_t* l, const kivi_cache_t* c, const v
                           float* out, void* workspace, size_t workspace_bytes, void* stream) {
     if (int s = check_layout(l)) return s;
     if (int s = check_cache(l, c)) return s;
-    if (!q || !out || !aligned16(q) || !aligned16(out)) return KIVI_ERR_INVALID_ARG;
-    const int length = c->n_kq + c->n_kr;
-    if (length < 1 || length != c->n_vq + c->n_vr) return KIVI_ERR_INVALID_ARG;
-    size_t need = 0;
-    kivi_decode_workspace_bytes(l, &need);
-    if (!workspace || !aligned16(workspace) || workspace_bytes < need) return KIVI_ERR_WORKSPACE;
+    if (int s = check_attention_args(l, c, q, out, workspace, workspace_bytes)) return s;
+    return enqueue_attention(l, c, q, softmax_scale, out, workspace, nullptr, nullptr, stream);
+}
 
-    DecodeParams p{};
-    p.k_codes = static_cast<const uint32_t*>(c->k_codes);
-    p.k_scale = static_cast<const __half*>(c->k_scale);
-    p.k_zero = static_cast<const __half*>(c->k_zero);
-    p.v_codes = static_cast<const uint32_t*>(c->v_codes);
-    p.v_scale = static_cast<const __half*>(c->v_scale);
-    p.v_zero = static_cast<const __half*>(c->v_zero);
-    p.k_resid = static_cast<const __half*>(c->k_resid);
-    p.v_resid = static_cast<const __half*>(c->v_resid);
-    p.n_kq = c->n_kq; p.n_vq = c->n_vq; p.k_r_start = c->k_r_start; p.n_kr = c->n_kr;
-    p.v_r_start = c->v_r_start; p.n_vr = c->n_vr;
-    p.cap_tiles = l->cap_q_tokens / kTileTokens; p.cap_r = l->cap_r_tokens;
-    p.q = static_cast<const __half*>(q); p.out = out;
-    p.softmax_scale = softmax_scale;
-    p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
-    p.length = length;
-    // the matrix-core family covers up to 4 query heads per kv-head; 8 run on the vector ALUs
-    const int rep = l->n_q_heads / l->n_kv_heads;
-    const int path = (l->decode_path == KIVI_DECODE_VALU || rep > 4) ? KIVI_DECODE_VALU : KIVI_DECODE_MFMA;
-    p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA ? kMfmaSplitTiles : kMaxSplitTiles);
-    const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
-    p.counters = static_cast<int32_t*>(workspace);
-    p.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(l));
-    p.part_ml = p.part_o + rows * kHeadDim;
-
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    hipError_t e = path == KIVI_DECODE_MFMA ? launch_decode_mfma(p, hs) : launch_decode_valu(p, hs);
-    if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
-    if (int s = hip_status(e)) return s;
-    // the matrix-core kernel merges its splits itself; the vector-ALU family uses a second launch
-    return path == KIVI_DECODE_MFMA ? KIVI_OK : hip_status(launch_merge(p, hs));
+int kivi_decode_step(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new, const void* v_new, const void* q,
+                     float softmax_scale, int32_t policy, float* out, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return KIVI_ERR_INVALID_ARG;
+    if (policy != KIVI_FLUSH_WINDOW && policy != KIVI_FLUSH_ALG1) return KIVI_ERR_INVALID_ARG;
+    if (c->n_kr >= l->cap_r_tokens || c->n_vr >= l->cap_r_tokens) return KIVI_ERR_INVALID_ARG;
+    // the cache as it will be after the append and the flush: everything is checked against it
+    // before anything is launched
+    kivi_cache_t after = *c;
+    after.n_kr += 1;
+    after.n_vr += 1;
+    int nk = 0, nv = 0;
+    if (int s = plan_flush(l, &after, policy, &nk, &nv)) return s;
+    {
+        kivi_cache_t fl = after;
+        fl.n_kq += nk; fl.n_kr -= nk; fl.n_vq += nv; fl.n_vr -= nv;
+        if (int s = check_attention_args(l, &fl, q, out, workspace, workspace_bytes)) return s;
+    }
+    if (nk == 0 && nv == 0 && decode_family(l) == KIVI_DECODE_MFMA) {
+        if (int s = enqueue_attention(l, &after, q, softmax_scale, out, workspace, k_new, v_new, stream)) return s;
+        *c = after;
+        return KIVI_OK;
+    }
+    if (int s = kivi_append_residual(l, c, k_new, v_new, stream)) return s;
+    if (int s = kivi_flush_residual(l, c, policy, nullptr, nullptr, stream)) return s;
+    return enqueue_attention(l, c, q, softmax_scale, out, workspace, nullptr, nullptr, stream);
 }
 
 }  // extern "C"

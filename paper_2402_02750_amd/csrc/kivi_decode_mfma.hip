@@ -44,17 +44,6 @@ constexpr int kVRow = 40;    // halves per column of the value-side B staging (8
 constexpr float kUnscale = 16777216.0f;                 // 2^24: codes enter as code * 2^-24
 constexpr float kDownscale = 1.0f / 16777216.0f;
 
-struct alignas(16) Half8 { __half2 v[4]; };
-
-__device__ __forceinline__ void unpack8(const Half8& h, float* f) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float2 t = __half22float2(h.v[i]);
-        f[2 * i] = t.x;
-        f[2 * i + 1] = t.y;
-    }
-}
-
 __device__ __forceinline__ int ring_slot(int start, int i, int cap) {
     int s = start + i;
     s -= (s >= cap) ? cap : 0;
@@ -563,6 +552,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
             const int tile0 = p.plan.tiles_a + (ck - u * n_b) * p.plan.tiles_per_split_b;
             const int n_tiles = min(p.plan.tiles_per_split_b, p.plan.tiles_total - tile0);
             const int64_t unit = u;
+            const bool fused_append = p.k_new != nullptr;
             const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
             const int64_t ubase = unit * p.cap_tiles + tile0;
             if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
@@ -586,8 +576,28 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
             auto load_value_row = [&](int tt, int j) -> half8 {
                 const int t = min(max(tt + j * 4 + (lane >> 4), p.n_vq), p.length - 1);
                 const int slot = ring_slot(p.v_r_start, t - p.n_vq, p.cap_r);
-                return *reinterpret_cast<const half8*>(p.v_resid + (unit * p.cap_r + slot) * kHeadDim + (lane & 15) * 8);
+                const __half* src = p.v_resid + (unit * p.cap_r + slot) * kHeadDim;
+                if (fused_append && t == p.length - 1) src = p.v_new + unit * kHeadDim;   // not in the ring yet
+                return *reinterpret_cast<const half8*>(src + (lane & 15) * 8);
             };
+            // Fused append: the wavefront that owns the tile of the newest token also stores that
+            // token's rows in the residual rings (lanes 0-15 the key row, 16-31 the value row).
+            // Nobody reads those slots in this launch -- every reader of token length-1 takes it from
+            // k_new / v_new -- and the row is requested here, long before it is stored.
+            bool owns_new = false;
+            uint4 new_row = {0u, 0u, 0u, 0u};
+            __half* new_dst = nullptr;
+            if (fused_append) {
+                const int last = p.length - 1, last_tile = last / kTileTokens;
+                owns_new = last_tile >= tile0 && last_tile < tile0 + n_tiles && ((last_tile - tile0) & 3) == wave && lane < 32;
+                if (owns_new) {
+                    const bool is_v = lane >= 16;
+                    const int slot = is_v ? ring_slot(p.v_r_start, last - p.n_vq, p.cap_r)
+                                          : ring_slot(p.k_r_start, last - p.n_kq, p.cap_r);
+                    new_row = *reinterpret_cast<const uint4*>((is_v ? p.v_new : p.k_new) + unit * kHeadDim + (lane & 15) * 8);
+                    new_dst = const_cast<__half*>(is_v ? p.v_resid : p.k_resid) + (unit * p.cap_r + slot) * kHeadDim + (lane & 15) * 8;
+                }
+            }
             half8 vr0[kPreloadV ? 8 : 1];
             if (kPreloadV) {
 #pragma unroll
@@ -624,7 +634,9 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
                         for (int j = 0; j < RB; ++j) {   // the batch's row loads first; rows past the end re-read the last row
                             const int t = min(tt + (j0 + j) * 4 + row, p.length - 1);
                             const int slot = ring_slot(p.k_r_start, t - p.n_kq, p.cap_r);
-                            kr[j] = *reinterpret_cast<const half8*>(p.k_resid + (unit * p.cap_r + slot) * kHeadDim + seg * 8);
+                            const __half* src = p.k_resid + (unit * p.cap_r + slot) * kHeadDim;
+                            if (fused_append && t == p.length - 1) src = p.k_new + unit * kHeadDim;   // not in the ring yet
+                            kr[j] = *reinterpret_cast<const half8*>(src + seg * 8);
                         }
 #pragma unroll
                         for (int hh = 0; hh < REP; ++hh) {
@@ -717,6 +729,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
             }
             }
             wave_lds_sync();
+            if (owns_new) *reinterpret_cast<uint4*>(new_dst) = new_row;
         }
     }
 

@@ -75,6 +75,9 @@ struct DecodeParams {
     const uint32_t* k_codes; const __half* k_scale; const __half* k_zero;
     const uint32_t* v_codes; const __half* v_scale; const __half* v_zero;
     const __half* k_resid; const __half* v_resid;
+    // fused append (matrix-core family only; null otherwise): the rows of token length-1, [b][H_kv][128].
+    // The kernel reads that token from here and writes it into the rings (which it may, then, modify).
+    const __half* k_new; const __half* v_new;
     int32_t n_kq, n_vq, k_r_start, n_kr, v_r_start, n_vr;
     int32_t cap_tiles, cap_r;
     // problem

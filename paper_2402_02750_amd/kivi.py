@@ -26,7 +26,7 @@ KIVI_DECODE_MFMA = 2
 EXPORTS = [
     "kivi_status_string", "kivi_cache_sizes", "kivi_decode_workspace_bytes",
     "kivi_quantize_key_groups", "kivi_quantize_value_tokens", "kivi_prefill", "kivi_append_residual",
-    "kivi_flush_residual", "kivi_decode_attention",
+    "kivi_flush_residual", "kivi_decode_attention", "kivi_decode_step",
 ]
 
 
@@ -79,6 +79,8 @@ def load_library() -> ctypes.CDLL:
     lib.kivi_flush_residual.argtypes = [P(kivi_layout_t), P(kivi_cache_t), I32, P(I32), P(I32), VP]
     lib.kivi_decode_attention.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, ctypes.c_float,
                                           VP, VP, ctypes.c_size_t, VP]
+    lib.kivi_decode_step.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, VP, VP, ctypes.c_float, I32,
+                                     VP, VP, ctypes.c_size_t, VP]
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -209,4 +211,20 @@ def kivi_decode_attention(layout, cache: Cache, q_fp16, softmax_scale, out_fp32,
         ctypes.c_float(softmax_scale), ctypes.c_void_p(out_fp32.data_ptr()),
         ctypes.c_void_p(cache.workspace.data_ptr()), cache.workspace.numel(),
         _stream_handle(stream)), "kivi_decode_attention")
+    return out_fp32
+
+
+def kivi_decode_step(layout, cache: Cache, k_new, v_new, q_fp16, softmax_scale, out_fp32,
+                     policy=KIVI_FLUSH_WINDOW, stream=None):
+    """Append + flush + attention of one decoding step.  k_new, v_new: contiguous CUDA fp16
+    [b, H_kv, 128] (keep them alive until the launch has run); q_fp16 / out_fp32 as for
+    kivi_decode_attention."""
+    assert k_new.is_contiguous() and v_new.is_contiguous()
+    assert q_fp16.is_contiguous() and out_fp32.is_contiguous()
+    _check(load_library().kivi_decode_step(
+        ctypes.byref(layout), ctypes.byref(cache.c), ctypes.c_void_p(k_new.data_ptr()),
+        ctypes.c_void_p(v_new.data_ptr()), ctypes.c_void_p(q_fp16.data_ptr()),
+        ctypes.c_float(softmax_scale), policy, ctypes.c_void_p(out_fp32.data_ptr()),
+        ctypes.c_void_p(cache.workspace.data_ptr()), cache.workspace.numel(),
+        _stream_handle(stream)), "kivi_decode_step")
     return out_fp32

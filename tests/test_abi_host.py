@@ -130,3 +130,30 @@ def test_entry_points_validate_before_launch(lib):
     assert lib.kivi_flush_residual(ctypes.byref(l), ctypes.byref(c), kivi.KIVI_FLUSH_WINDOW,
                                    ctypes.byref(nk), ctypes.byref(nv), None) == kivi.KIVI_OK
     assert (nk.value, nv.value) == (0, 0) and c.n_kr == 70
+
+
+def test_decode_step_validates_before_launch(lib):
+    l = _layout()
+    good_ptr = ctypes.c_void_p(0x2000)
+    out = ctypes.c_void_p(0x3000)
+    f = lib.kivi_decode_step
+
+    def call(c, k_new=good_ptr, v_new=good_ptr, q=good_ptr, policy=kivi.KIVI_FLUSH_WINDOW, ws=good_ptr, ws_bytes=1 << 30):
+        before = bytes(c)
+        st = f(ctypes.byref(l), ctypes.byref(c), k_new, v_new, q, 0.1, policy, out, ws, ws_bytes, None)
+        assert bytes(c) == before, "the cache must be unchanged on an error"
+        return st
+
+    c = _fake_cache(n_kq=64, n_kr=3, n_vq=64, n_vr=3)
+    assert call(c, k_new=None) == kivi.KIVI_ERR_INVALID_ARG
+    assert call(c, v_new=ctypes.c_void_p(0x2004)) == kivi.KIVI_ERR_INVALID_ARG
+    assert call(c, q=None) == kivi.KIVI_ERR_INVALID_ARG
+    assert call(c, policy=7) == kivi.KIVI_ERR_INVALID_ARG
+    assert call(c, ws=None, ws_bytes=0) == kivi.KIVI_ERR_WORKSPACE
+    assert call(c, ws_bytes=64) == kivi.KIVI_ERR_WORKSPACE
+    # full ring
+    assert call(_fake_cache(n_kq=64, n_kr=96, n_vq=64, n_vr=96)) == kivi.KIVI_ERR_INVALID_ARG
+    # the flush that this step triggers does not fit the quantised capacity (256 tokens)
+    assert call(_fake_cache(n_kq=256, n_kr=95, n_vq=256, n_vr=95)) == kivi.KIVI_ERR_INVALID_ARG
+    # WINDOW policy needs the symmetric split
+    assert call(_fake_cache(n_kq=64, n_kr=10, n_vq=32, n_vr=42)) == kivi.KIVI_ERR_INVALID_ARG
