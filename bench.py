@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # scaled by the factor a plain copy kernel of known size reads on the same counters; see the
 # summaries under profiles/.  None until measured for a workload/path.
 MEASURED_TRAFFIC = {
-    # profiles/decode_mfma_llama7b.md: FETCH_SIZE 112237.3 KiB x 2.0 + WRITE_SIZE 880.0 KiB x 1.0
-    ("llama7b", "mfma"): 112237.3 * 1024 * 2.0 + 880.0 * 1024,
-    ("llama7b", "auto"): 112237.3 * 1024 * 2.0 + 880.0 * 1024,
+    # profiles/decode_mfma_llama7b.md: FETCH_SIZE 111887.1 KiB x 2.0 + WRITE_SIZE 387.1 KiB x 1.0
+    ("llama7b", "mfma"): 111887.1 * 1024 * 2.0 + 387.1 * 1024,
+    ("llama7b", "auto"): 111887.1 * 1024 * 2.0 + 387.1 * 1024,
 }
 
 
@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=500,
                     help="untimed steps; a few hundred let the clocks settle (a step is ~50 us)")
-    ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "llama13b_4bit", "mistral_gqa"])
+    ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "stream", "llama13b_4bit", "mistral_gqa"])
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--copies", type=int, default=5)
     ap.add_argument("--context", type=int, default=0, help="override the workload's context length (scaling studies)")
@@ -82,6 +82,70 @@ def cpu_baseline(w, k, v, q, seconds):
                       f"{t_total:.1f} s, scaled to all units"}
 
 
+def run_stream(args, w, path_name, path):
+    """Streaming workload: prefill `prompt` tokens, then `decode_steps` single-token steps through
+    kivi_decode_step (append, flush of one group every G steps, attention).  One untimed pass of all
+    steps, then the same steps timed; a step here is one of the workload's decode steps, so --steps
+    and --warmup are fixed to the workload's step count."""
+    import numpy as np
+    import torch
+    from paper_2402_02750_amd import kivi, workloads
+
+    total = w.prompt + w.decode_steps
+    k, v = workloads.keys(w, total), workloads.values(w, total)
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    del k, v
+    qs = torch.from_numpy(np.stack([workloads.queries(w, s) for s in range(w.decode_steps)])).cuda()
+    k_new = [kt[:, :, w.prompt + s].contiguous() for s in range(w.decode_steps)]
+    v_new = [vt[:, :, w.prompt + s].contiguous() for s in range(w.decode_steps)]
+    cap_q = (total + 31) // 32 * 32
+    layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, cap_q,
+                              w.residual + w.group + 32, decode_path=path)
+    cache = kivi.Cache(layout)
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def one_pass():
+        cache.c.n_kq = cache.c.n_vq = cache.c.n_kr = cache.c.n_vr = 0
+        kivi.kivi_prefill(layout, kt, vt, w.prompt, cache)
+        bytes_total, flushes = 0, 0
+        ev0.record(stream)
+        for s in range(w.decode_steps):
+            before = cache.c.n_kq
+            kivi.kivi_decode_step(layout, cache, k_new[s], v_new[s], qs[s], w.softmax_scale, out,
+                                  kivi.KIVI_FLUSH_WINDOW, stream)
+            flushes += cache.c.n_kq != before
+            bytes_total += w.algorithmic_bytes(cache.c.n_kq, cache.c.n_kr)["all"]
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1), bytes_total, flushes
+
+    one_pass()
+    ms, bytes_total, flushes = one_pass()
+    achieved = bytes_total / (ms * 1e-3) / 1e9
+    return {
+        "metric": "decode-attn tokens/s over 2-bit KV; achieved HBM GB/s vs MI355X peak",
+        "value": w.batch * w.decode_steps / (ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": w.decode_steps, "warmup": w.decode_steps,
+        "ms_per_step": ms / w.decode_steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": f"u{w.bits} codes, fp16 scale/zero/residual, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads, head_dim 128, "
+                               f"prompt {w.prompt} + {w.decode_steps} decode steps, {w.bits}-bit, G=32, R={w.residual}, "
+                               f"{flushes} flushes of one group",
+                   "decode_path": path_name,
+                   "step": "kivi_decode_step: append newest token + flush (every 32nd step) + decode attention"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "whole steps (attention kernel plus, on flush steps, the copy and quantise kernels): "
+                               "sum of the attention's algorithmic bytes over the steps / time of all steps",
+                     "algorithmic_bytes_per_launch": bytes_total / w.decode_steps},
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -97,6 +161,10 @@ def main():
     kivi.load_library()
     torch.cuda.set_device(0)
     w = workloads.CONFIGS[args.workload]
+    if w.decode_steps:
+        path = {"auto": kivi.KIVI_DECODE_AUTO, "valu": kivi.KIVI_DECODE_VALU, "mfma": kivi.KIVI_DECODE_MFMA}[args.path]
+        print(json.dumps(run_stream(args, w, args.path, path)))
+        return
     if args.context:
         w = workloads.scaled(w, name=f"{w.name}@{args.context}", context=args.context)
     n_q, n_r = w.split_single_step()
