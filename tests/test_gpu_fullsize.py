@@ -53,9 +53,9 @@ def test_single_step_configs(name, n_heads, path):
 
 
 def test_streaming_config3():
-    """BASELINE config 3: batch 64, prompt 2048, 256 decode steps with a flush every 32 steps.
-    Cache state is compared bit-exactly after every flush and outputs at every step, on a sample
-    of units."""
+    """BASELINE config 3: batch 64, prompt 2048, 256 decode steps (kivi_decode_step) with a flush
+    every 32 steps.  Cache state is compared bit-exactly after every flush and every 16th step
+    (the rings must hold what the fused append stored), outputs at every step, on a sample of units."""
     torch = gh.require_gpu()
     w = CONFIGS["stream"]
     total = w.prompt + w.decode_steps
@@ -71,17 +71,20 @@ def test_streaming_config3():
     flushes, worst = [], 0.0
     for step in range(1, w.decode_steps + 1):
         t = w.prompt + step - 1
-        kivi.kivi_append_residual(layout, cache, kt[:, :, t].contiguous(), vt[:, :, t].contiguous())
-        nk, nv = kivi.kivi_flush_residual(layout, cache, kivi.KIVI_FLUSH_WINDOW)
+        q = workloads.queries(w, step)
+        before = cache.c.n_kq
+        # the call bench.py times: append + flush + attention, one launch on the steps without a flush
+        kivi.kivi_decode_step(layout, cache, kt[:, :, t].contiguous(), vt[:, :, t].contiguous(),
+                              torch.from_numpy(q).cuda(), w.softmax_scale, out, kivi.KIVI_FLUSH_WINDOW)
+        nk = cache.c.n_kq - before
         knew = np.stack([k[b, h, t] for b, h in heads])[:, None]
         vnew = np.stack([v[b, h, t] for b, h in heads])[:, None]
-        assert (nk, nv) == oc.append(knew, vnew)
-        if nk:
-            flushes.append(step)
+        assert (nk, nk) == oc.append(knew, vnew)
+        if nk or step % 16 == 1:
+            if nk:
+                flushes.append(step)
             torch.cuda.synchronize()
             gh.compare_quantized_state(cache, oc, heads)
-        q = workloads.queries(w, step)
-        kivi.kivi_decode_attention(layout, cache, torch.from_numpy(q).cuda(), w.softmax_scale, out)
         ref = gh.oracle_attention_for_heads(w, oc, q, heads)
         worst = max(worst, gh.check_close(gh.pick_heads(out.cpu().numpy(), w, heads), ref, f"step {step}"))
         if step % 32 == 0:
