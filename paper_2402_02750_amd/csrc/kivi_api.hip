@@ -62,33 +62,36 @@ int max_splits(const kivi_layout_t* l) {
     return tiles;   // every split covers at least one tile
 }
 
-SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, int max_tiles) {
+// `mfma`: plan for the persistent matrix-core kernel (fixed chunk length, resident workgroups known);
+// otherwise for the vector-ALU family.
+SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, bool mfma) {
     SplitPlan s{};
     const int length = c->n_kq + c->n_kr;
     s.tiles_a = std::min(c->n_kq, c->n_vq) / kTileTokens;
     s.tiles_total = ceil_div(length, kTileTokens);
-    // Aim at ~16 workgroups per compute unit in flight over the whole grid so the 256 CUs stay
-    // busy through the tail, but keep splits long enough that the per-split partial results
-    // (520 B per query head) stay a small fraction of the bytes a split streams.
     const int64_t units = (int64_t)l->batch * l->n_kv_heads;
-    const int64_t target_wgs = 4096;
     const int rep = l->n_q_heads / l->n_kv_heads;
-    int tps = (int)std::min<int64_t>(max_tiles, ((int64_t)s.tiles_a * units + target_wgs - 1) / target_wgs);
-    tps = std::max(tps, std::min(max_tiles, 4 * rep));
-    s.tiles_per_split_a = std::max(1, std::min(tps, max_tiles));
-    // The persistent matrix-core kernel always walks full 16-tile chunks (4 slots per wavefront):
-    // shorter chunks would only re-read masked tiles.
-    if (max_tiles == kMfmaSplitTiles) s.tiles_per_split_a = kMfmaSplitTiles;
-    // fp16 rows cost 512 B per token against 96 B (2-bit) or 160 B (4-bit)
-    const int packed_per_tile = kTileTokens * 2 * (kHeadDim * l->bits / 8 + 16);
-    const int fp16_per_tile = kTileTokens * 2 * kHeadDim * 2;
     const int tiles_b = s.tiles_total - s.tiles_a;
-    int tps_b_max = std::max(1, std::min(8, s.tiles_per_split_a * packed_per_tile / fp16_per_tile));
-    if (max_tiles == kMfmaSplitTiles) {
-        // persistent matrix-core kernel: ~512 resident workgroups each take an equal count of fp16-row
-        // chunks, so make the chunks as long as possible while every workgroup still gets one
-        // (4 tiles = one per wavefront is the natural size)
-        tps_b_max = (int)std::max<int64_t>(1, std::min<int64_t>(kMfmaSplitTiles, units * tiles_b / 512));
+    int tps_b_max;
+    if (mfma) {
+        // The kernel always walks full chunks (shorter ones would only re-read masked tiles).  Its
+        // resident workgroups each take an equal count of fp16-row chunks, so make those as long as
+        // possible while every workgroup still gets one (4 tiles = one per wavefront is the natural size).
+        const MfmaGeometry g = mfma_geometry(l->bits, rep);
+        s.tiles_per_split_a = g.chunk_tiles;
+        tps_b_max = (int)std::max<int64_t>(1, std::min<int64_t>(kMfmaSplitTiles, units * tiles_b / g.resident_workgroups));
+    } else {
+        // Aim at ~16 workgroups per compute unit in flight over the whole grid so the 256 CUs stay
+        // busy through the tail, but keep splits long enough that the per-split partial results
+        // (520 B per query head) stay a small fraction of the bytes a split streams.
+        const int64_t target_wgs = 4096;
+        int tps = (int)std::min<int64_t>(kMaxSplitTiles, ((int64_t)s.tiles_a * units + target_wgs - 1) / target_wgs);
+        tps = std::max(tps, std::min(kMaxSplitTiles, 4 * rep));
+        s.tiles_per_split_a = std::max(1, std::min(tps, kMaxSplitTiles));
+        // fp16 rows cost 512 B per token against 96 B (2-bit) or 160 B (4-bit)
+        const int packed_per_tile = kTileTokens * 2 * (kHeadDim * l->bits / 8 + 16);
+        const int fp16_per_tile = kTileTokens * 2 * kHeadDim * 2;
+        tps_b_max = std::max(1, std::min(8, s.tiles_per_split_a * packed_per_tile / fp16_per_tile));
     }
     s.n_splits_b = ceil_div(tiles_b, tps_b_max);
     s.tiles_per_split_b = s.n_splits_b ? ceil_div(tiles_b, s.n_splits_b) : 1;     // even out the pieces
@@ -190,7 +193,7 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     const int path = decode_family(l);
     if ((k_new || v_new) && path != KIVI_DECODE_MFMA) return KIVI_ERR_UNSUPPORTED;
     p.k_new = static_cast<const __half*>(k_new); p.v_new = static_cast<const __half*>(v_new);
-    p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA ? kMfmaSplitTiles : kMaxSplitTiles);
+    p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA);
     const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
     p.counters = static_cast<int32_t*>(workspace);
     p.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(l));

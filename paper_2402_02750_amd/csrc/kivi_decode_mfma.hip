@@ -31,14 +31,19 @@
 
 #include <algorithm>
 
+#ifndef KIVI_V21_SLOTS
+#define KIVI_V21_SLOTS 4
+#define KIVI_V21_OCC 2
+#endif
+
 namespace kivi {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-constexpr int kSlots = kMfmaSplitTiles / 4;             // tile slots per wavefront (4)
-constexpr int kWaveTokens = kSlots * kTileTokens;       // 128
+constexpr int kMaxSlots = kMfmaSplitTiles / 4;          // most tile slots per wavefront (4)
+constexpr int kWaveTokens = kMaxSlots * kTileTokens;    // 128: token slots of a wavefront's LDS rows
 constexpr int kKRow = 136;   // halves per column of the key-side B staging (272 B: bank skew)
 constexpr int kVRow = 40;    // halves per column of the value-side B staging (80 B: bank skew)
 constexpr float kUnscale = 16777216.0f;                 // 2^24: codes enter as code * 2^-24
@@ -156,16 +161,16 @@ __device__ __forceinline__ float join_hi_lo(float hi, float lo) { return fmaf(lo
 // LDS of one wavefront.  `lr` holds, per matrix column (head, hi/lo), the raw matrix-core logits
 // of the wave's 128 token slots; after the softmax the hi column of a head holds its
 // probabilities and the lo column becomes the head's output staging row.
-template <int REP>
+template <int REP, int SS>
 struct WaveLds {
     static constexpr int NC = 2 * REP;
-    static constexpr int kStageSlots = REP <= 2 ? 2 : 1;   // tile slots staged at once (register pressure)
+    static constexpr int kStageSlots = SS;              // tile slots staged at once
     static constexpr int kKSlot = NC * kKRow;          // halves per staged key-side operand
     static constexpr int kVSlot = 4 * NC * kVRow;      // halves per staged value-side operand
     static constexpr int kBHalves = kStageSlots * (kKSlot > kVSlot ? kKSlot : kVSlot);
     __align__(16) float lr[NC][kWaveTokens];
     __align__(16) __half b[kBHalves];
-    __align__(16) float zt[NC][kSlots];
+    __align__(16) float zt[NC][kMaxSlots];
 };
 
 // Write the key-side small operand of one tile: columns (2hh, 2hh+1) = hi/lo of q_c s_c / posfactor.
@@ -244,15 +249,20 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
                                                         acc[u], 0, 0, 0);
 }
 
-template <int BITS, int REP>
-__global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
-    using WL = WaveLds<REP>;
+// SLOTS: tile slots per wavefront of an all-quantised chunk (chunk = 4 * SLOTS tiles); OCC: workgroups
+// per compute unit the register budget is sized for.
+template <int BITS, int REP, int SLOTS, int OCC>
+__global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
+    constexpr int kSlots = SLOTS;
+    // tile slots staged at once: two where that divides the slots and the registers allow
+    constexpr int kStage = REP > 2 ? 1 : (SLOTS % 2 == 0 ? 2 : SLOTS);
+    using WL = WaveLds<REP, kStage>;
     constexpr int NC = 2 * REP;                       // live matrix columns: (head, hi/lo)
     constexpr int SS = WL::kStageSlots;
     // fp16-row chunks: rows held in registers at once, and whether the first tile's value rows are
     // requested ahead of the logits (both cut for the wider instantiations: register pressure)
-    constexpr int RB = 8;
-    constexpr bool kPreloadV = true;
+    constexpr int RB = OCC >= 3 ? 4 : 8;
+    constexpr bool kPreloadV = OCC < 3;
     __shared__ __align__(16) float sm_q[REP][kHeadDim];               // scale * q
     __shared__ __align__(16) __half sm_qf[NC][kKRow];                 // its hi/lo columns (z-term operand)
     __shared__ WL sm_w[4];
@@ -555,7 +565,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
             const bool fused_append = p.k_new != nullptr;
             const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
             const int64_t ubase = unit * p.cap_tiles + tile0;
-            if (lane < NC * kSlots) (&wl.zt[0][0])[lane] = 0.f;
+            if (lane < NC * kMaxSlots) (&wl.zt[0][0])[lane] = 0.f;
             // how many of the wave's tiles are quantised key tiles (they come first in token order)
             int cnt_kq = 0;
             for (int i = 0; i < cnt; ++i) cnt_kq += ((tile0 + wave + 4 * i) * kTileTokens < p.n_kq) ? 1 : 0;
@@ -809,55 +819,74 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeParams p) {
 }
 
 // Workgroups the chip holds at once for one instantiation (occupancy query, cached).
-template <int BITS, int REP>
+template <int BITS, int REP, int SLOTS, int OCC>
 int resident_workgroups() {
     static int cached = 0;
     if (cached == 0) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP>, 256, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC>, 256, 0) != hipSuccess ||
             cus <= 0 || per_cu <= 0)
-            return 256;
+            return 256 * OCC;
         cached = cus * per_cu;
     }
     return cached;
 }
 
-template <int BITS, int REP>
+template <int BITS, int REP, int SLOTS, int OCC>
 hipError_t launch_one(DecodeParams p, hipStream_t stream) {
+    if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
     const int64_t units = (int64_t)p.batch * p.n_kv_heads;
     const int64_t total_a = units * p.plan.n_splits_a, total_b = units * p.plan.n_splits_b;
     if (total_a + total_b > 0x7fffffff) return hipErrorInvalidValue;
     // every resident workgroup gets an equal share of both kinds of chunks
-    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP>(), std::max(total_a, total_b)));
+    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC>(), std::max(total_a, total_b)));
     p.total_chunks_a = (int)total_a;
     p.total_chunks_b = (int)total_b;
     p.chunks_per_wg_a = (int)std::max<int64_t>(1, (total_a + slots - 1) / slots);
     p.chunks_per_wg_b = (int)std::max<int64_t>(1, (total_b + slots - 1) / slots);
     const int grid = (int)std::max((total_a + p.chunks_per_wg_a - 1) / p.chunks_per_wg_a,
                                    (total_b + p.chunks_per_wg_b - 1) / p.chunks_per_wg_b);
-    decode_mfma_kernel<BITS, REP><<<grid, 256, 0, stream>>>(p);
+    decode_mfma_kernel<BITS, REP, SLOTS, OCC><<<grid, 256, 0, stream>>>(p);
     return hipGetLastError();
 }
 
-template <int BITS>
-hipError_t launch_bits(const DecodeParams& p, hipStream_t stream) {
-    const int rep = p.n_q_heads / p.n_kv_heads;
-    if (p.plan.tiles_per_split_a > kMfmaSplitTiles || p.plan.tiles_per_split_b > kMfmaSplitTiles)
-        return hipErrorInvalidValue;
-    switch (rep) {
-        case 1: return launch_one<BITS, 1>(p, stream);
-        case 2: return launch_one<BITS, 2>(p, stream);
-        case 4: return launch_one<BITS, 4>(p, stream);
-        default: return hipErrorNotSupported;   // 8 query heads per kv-head: vector-ALU family
-    }
+// The instantiation that serves (bits, query heads per kv-head): tile slots per wavefront and
+// workgroups per compute unit.  `fn` is called with the four template arguments as a tag.
+template <int B, int R, int S, int O> struct Variant {
+    static constexpr int bits = B, rep = R, slots = S, occ = O;
+};
+template <class F>
+bool with_variant(int bits, int rep, F&& fn) {
+    if (bits == 2 && rep == 1) { fn(Variant<2, 1, KIVI_V21_SLOTS, KIVI_V21_OCC>{}); return true; }
+    if (bits == 2 && rep == 2) { fn(Variant<2, 2, 4, 2>{}); return true; }
+    if (bits == 2 && rep == 4) { fn(Variant<2, 4, 4, 2>{}); return true; }
+    if (bits == 4 && rep == 1) { fn(Variant<4, 1, 4, 2>{}); return true; }
+    if (bits == 4 && rep == 2) { fn(Variant<4, 2, 4, 2>{}); return true; }
+    if (bits == 4 && rep == 4) { fn(Variant<4, 4, 4, 2>{}); return true; }
+    return false;                       // 8 query heads per kv-head: vector-ALU family
 }
 
 }  // namespace
 
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
-    return p.bits == 2 ? launch_bits<2>(p, stream) : launch_bits<4>(p, stream);
+    hipError_t e = hipErrorNotSupported;
+    with_variant(p.bits, p.n_q_heads / p.n_kv_heads, [&](auto v) {
+        using V = decltype(v);
+        e = launch_one<V::bits, V::rep, V::slots, V::occ>(p, stream);
+    });
+    return e;
+}
+
+MfmaGeometry mfma_geometry(int bits, int rep) {
+    MfmaGeometry g{kMfmaSplitTiles, 512};
+    with_variant(bits, rep, [&](auto v) {
+        using V = decltype(v);
+        g.chunk_tiles = 4 * V::slots;
+        g.resident_workgroups = resident_workgroups<V::bits, V::rep, V::slots, V::occ>();
+    });
+    return g;
 }
 
 }  // namespace kivi

@@ -102,4 +102,9 @@ hipError_t launch_decode_valu(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_merge(const DecodeParams& p, hipStream_t stream);
 
+// Chunk length (tiles) of all-quantised chunks and resident workgroups of the matrix-core instantiation
+// that serves (bits, query heads per kv-head); the split planner and the kernel must agree on both.
+struct MfmaGeometry { int chunk_tiles, resident_workgroups; };
+MfmaGeometry mfma_geometry(int bits, int rep);
+
 }  // namespace kivi
