@@ -74,12 +74,12 @@ SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, bool mfma) 
     const int tiles_b = s.tiles_total - s.tiles_a;
     int tps_b_max;
     if (mfma) {
-        // The kernel always walks full chunks (shorter ones would only re-read masked tiles).  Its
-        // resident workgroups each take an equal count of fp16-row chunks, so make those as long as
-        // possible while every workgroup still gets one (4 tiles = one per wavefront is the natural size).
+        // The kernel always walks full chunks (shorter ones would only re-read masked tiles).  The
+        // natural fp16-row chunk is 4 tiles, one per wavefront; shorter ones when there would be
+        // fewer chunks than resident workgroups.
         const MfmaGeometry g = mfma_geometry(l->bits, rep);
         s.tiles_per_split_a = g.chunk_tiles;
-        tps_b_max = (int)std::max<int64_t>(1, std::min<int64_t>(kMfmaSplitTiles, units * tiles_b / g.resident_workgroups));
+        tps_b_max = (int)std::max<int64_t>(1, std::min<int64_t>(4, units * tiles_b / g.resident_workgroups));
     } else {
         // Aim at ~16 workgroups per compute unit in flight over the whole grid so the 256 CUs stay
         // busy through the tail, but keep splits long enough that the per-split partial results

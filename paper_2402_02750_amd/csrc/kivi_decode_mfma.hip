@@ -282,8 +282,19 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     const int n_a = p.plan.n_splits_a, n_b = p.plan.n_splits_b;   // chunks per unit: all-quantised / with fp16 rows
     const int cpu = n_a + n_b;
     // this workgroup's ranges in the two global chunk index spaces (unit-major)
-    const int first_a = blockIdx.x * p.chunks_per_wg_a, last_a = min(first_a + p.chunks_per_wg_a, p.total_chunks_a);
-    const int first_b = blockIdx.x * p.chunks_per_wg_b, last_b = min(first_b + p.chunks_per_wg_b, p.total_chunks_b);
+    const int64_t cost_total = p.total_cost;
+    const int n_wgs = gridDim.x, cost_unit = p.cost_unit, cost_b = p.cost_b;
+    auto owner = [&](int64_t pos) -> int {                 // workgroup whose cost interval holds `pos`
+        return (int)(((pos + 1) * n_wgs - 1) / cost_total);
+    };
+    auto chunks_before = [&](int64_t pos, int& nb, int& na) {   // chunks of either kind that start before `pos`
+        const int u = (int)(pos / cost_unit), r = (int)(pos - (int64_t)u * cost_unit);
+        nb = u * n_b + min(n_b, (r + cost_b - 1) / cost_b);
+        na = u * n_a + min(max(r - n_b * cost_b, 0), n_a);
+    };
+    int first_a, last_a, first_b, last_b;
+    chunks_before((int64_t)blockIdx.x * cost_total / n_wgs, first_b, first_a);
+    chunks_before((int64_t)(blockIdx.x + 1) * cost_total / n_wgs, last_b, last_a);
 
     // registers holding the packed data of one all-quantised chunk (4 slots of this wavefront)
     uint32_t kw[kSlots][kLaneWords], vw[kSlots][kLaneWords];
@@ -349,10 +360,11 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 
     // workgroups whose all-quantised range / fp16-row range touches unit u: first index and count
     auto contributors = [&](int u, int& ga0, int& len_a, int& gb0, int& len_b) {
-        ga0 = n_a ? (u * n_a) / p.chunks_per_wg_a : 0;
-        len_a = n_a ? ((u + 1) * n_a - 1) / p.chunks_per_wg_a - ga0 + 1 : 0;
-        gb0 = n_b ? (u * n_b) / p.chunks_per_wg_b : 0;
-        len_b = n_b ? ((u + 1) * n_b - 1) / p.chunks_per_wg_b - gb0 + 1 : 0;
+        const int64_t base = (int64_t)u * cost_unit, a0 = base + n_b * cost_b;
+        gb0 = n_b ? owner(base) : 0;
+        len_b = n_b ? owner(base + (n_b - 1) * cost_b) - gb0 + 1 : 0;
+        ga0 = n_a ? owner(a0) : 0;
+        len_a = n_a ? owner(a0 + n_a - 1) - ga0 + 1 : 0;
     };
 
     // ---- leave a unit: merge the four wavefronts, write the output or this workgroup's part ----
@@ -839,15 +851,18 @@ hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
     const int64_t units = (int64_t)p.batch * p.n_kv_heads;
     const int64_t total_a = units * p.plan.n_splits_a, total_b = units * p.plan.n_splits_b;
-    if (total_a + total_b > 0x7fffffff) return hipErrorInvalidValue;
-    // every resident workgroup gets an equal share of both kinds of chunks
-    const int64_t slots = std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC>(), std::max(total_a, total_b)));
+    // cost of an fp16-row chunk in units of an all-quantised chunk: by the bytes they stream
+    const int64_t bytes_a = (int64_t)4 * SLOTS * kTileTokens * 2 * (kHeadDim * BITS / 8 + 16);
+    const int64_t bytes_b = (int64_t)p.plan.tiles_per_split_b * kTileTokens * 2 * kHeadDim * 2;
+    p.cost_b = (int)std::max<int64_t>(1, (bytes_b + bytes_a / 2) / bytes_a);
+    p.cost_unit = p.plan.n_splits_b * p.cost_b + p.plan.n_splits_a;
+    p.total_cost = units * p.cost_unit;
+    if (p.total_cost <= 0 || p.total_cost > 0x3fffffff || total_a + total_b > 0x7fffffff) return hipErrorInvalidValue;
     p.total_chunks_a = (int)total_a;
     p.total_chunks_b = (int)total_b;
-    p.chunks_per_wg_a = (int)std::max<int64_t>(1, (total_a + slots - 1) / slots);
-    p.chunks_per_wg_b = (int)std::max<int64_t>(1, (total_b + slots - 1) / slots);
-    const int grid = (int)std::max((total_a + p.chunks_per_wg_a - 1) / p.chunks_per_wg_a,
-                                   (total_b + p.chunks_per_wg_b - 1) / p.chunks_per_wg_b);
+    // every resident workgroup gets an equal share of the cost axis (within one unit of cost)
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC>(),
+                                                                  p.total_cost / p.cost_b));
     decode_mfma_kernel<BITS, REP, SLOTS, OCC><<<grid, 256, 0, stream>>>(p);
     return hipGetLastError();
 }

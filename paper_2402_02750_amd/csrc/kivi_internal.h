@@ -89,9 +89,12 @@ struct DecodeParams {
     float softmax_scale;
     int32_t batch, n_q_heads, n_kv_heads, bits, length;
     SplitPlan plan;
-    // persistent matrix-core kernel: chunk = (unit, split) in two unit-major index spaces (all-quantised
-    // splits / splits with fp16 rows); workgroup g walks [g*cpw, (g+1)*cpw) of each
-    int32_t total_chunks_a, chunks_per_wg_a, total_chunks_b, chunks_per_wg_b;
+    // Persistent matrix-core kernel.  Work lies on a cost axis: unit u occupies [u * cost_unit,
+    // (u + 1) * cost_unit): first its fp16-row chunks (cost_b each), then its all-quantised chunks
+    // (cost 1 each).  Workgroup g of G owns the chunks that start in [g * T / G, (g + 1) * T / G),
+    // T = units * cost_unit.
+    int32_t total_chunks_a, total_chunks_b, cost_b, cost_unit;
+    int64_t total_cost;
 };
 
 // launchers (each defined next to its kernels); they return hipGetLastError() after the launch
