@@ -282,19 +282,27 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     const int n_a = p.plan.n_splits_a, n_b = p.plan.n_splits_b;   // chunks per unit: all-quantised / with fp16 rows
     const int cpu = n_a + n_b;
     // this workgroup's ranges in the two global chunk index spaces (unit-major)
-    const int64_t cost_total = p.total_cost;
+    // Index arithmetic on the cost axis; 32-bit whenever the products fit (64-bit division costs
+    // more than a hundred instructions each and every workgroup does about a dozen).
     const int n_wgs = gridDim.x, cost_unit = p.cost_unit, cost_b = p.cost_b;
+    const bool small_axis = (p.total_cost + 1) * n_wgs < 0x7fffffffLL;
+    auto wg_start = [&](int g) -> int64_t {                // first cost position of workgroup g
+        return small_axis ? (int64_t)((uint32_t)g * (uint32_t)p.total_cost / (uint32_t)n_wgs)
+                          : (int64_t)g * p.total_cost / n_wgs;
+    };
     auto owner = [&](int64_t pos) -> int {                 // workgroup whose cost interval holds `pos`
-        return (int)(((pos + 1) * n_wgs - 1) / cost_total);
+        return small_axis ? (int)((((uint32_t)pos + 1u) * (uint32_t)n_wgs - 1u) / (uint32_t)p.total_cost)
+                          : (int)(((pos + 1) * n_wgs - 1) / p.total_cost);
     };
     auto chunks_before = [&](int64_t pos, int& nb, int& na) {   // chunks of either kind that start before `pos`
-        const int u = (int)(pos / cost_unit), r = (int)(pos - (int64_t)u * cost_unit);
+        const int u = small_axis ? (int)((uint32_t)pos / (uint32_t)cost_unit) : (int)(pos / cost_unit);
+        const int r = (int)(pos - (int64_t)u * cost_unit);
         nb = u * n_b + min(n_b, (r + cost_b - 1) / cost_b);
         na = u * n_a + min(max(r - n_b * cost_b, 0), n_a);
     };
     int first_a, last_a, first_b, last_b;
-    chunks_before((int64_t)blockIdx.x * cost_total / n_wgs, first_b, first_a);
-    chunks_before((int64_t)(blockIdx.x + 1) * cost_total / n_wgs, last_b, last_a);
+    chunks_before(wg_start(blockIdx.x), first_b, first_a);
+    chunks_before(wg_start(blockIdx.x + 1), last_b, last_a);
 
     // registers holding the packed data of one all-quantised chunk (4 slots of this wavefront)
     uint32_t kw[kSlots][kLaneWords], vw[kSlots][kLaneWords];
