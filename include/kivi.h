@@ -27,12 +27,16 @@
  *   x' = code * s + z.
  *
  * Memory layout (all arrays dense, index order as written, b = batch entry, h = kv-head)
- *   k_codes  uint32 [b][h][cap_q/32][W]   one "key tile" per group of 32 tokens, W = 32*128*B/32
- *   k_scale  fp16   [b][h][cap_q/32][128]  per (group, channel)
+ *   k_codes  uint32 [b][h][cap_q/32][W]   one "key tile" per block of 32 tokens, W = 32*128*B/32
+ *   k_scale  fp16   [b][h][cap_q/32][128]  per (tile, channel)
  *   k_zero   fp16   [b][h][cap_q/32][128]
  *   v_codes  uint32 [b][h][cap_q/32][W]   one "value tile" per block of 32 tokens
- *   v_scale  fp16   [b][h][cap_q][4]       per (token, group of 32 channels)
+ *   v_scale  fp16   [b][h][cap_q][4]       per (token, block of 32 channels)
  *   v_zero   fp16   [b][h][cap_q][4]
+ *   Scales and zero-points are kept at this 32-token / 32-channel granularity for every G: with
+ *   G = 64 or 128 a group's pair is stored in each of the G/32 tiles (blocks) it covers, so the
+ *   decode kernels read the same arrays whatever G is (the scale bytes a larger G would save are
+ *   not saved).
  *   k_resid  fp16   [b][h][cap_r][128]     ring buffer: the i-th oldest residual token is in slot
  *   v_resid  fp16   [b][h][cap_r][128]     (r_start + i) % cap_r
  *   q        fp16   [b][n_q_heads][128]
@@ -82,9 +86,9 @@ typedef struct kivi_layout {
     int32_t n_kv_heads;     /* key/value heads                                            */
     int32_t head_dim;       /* D; this build supports 128                                 */
     int32_t bits;           /* B: 2 or 4                                                  */
-    int32_t group;          /* G: this build supports 32                                  */
+    int32_t group;          /* G: 32, 64 or 128 (tokens per key group, channels per value group) */
     int32_t residual;       /* R: residual length, a multiple of G (Section 3.3)          */
-    int32_t cap_q_tokens;   /* capacity of the quantised part in tokens, multiple of 32   */
+    int32_t cap_q_tokens;   /* capacity of the quantised part in tokens, multiple of G    */
     int32_t cap_r_tokens;   /* capacity of each fp16 ring in tokens, multiple of 32, >= R + G */
     int32_t decode_path;    /* KIVI_DECODE_*                                              */
 } kivi_layout_t;

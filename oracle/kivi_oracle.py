@@ -45,7 +45,7 @@ from __future__ import annotations
 
 import numpy as np
 
-TILE_TOKENS = 32  # tokens per packed code tile (= the group size G the ABI supports)
+TILE_TOKENS = 32  # tokens per packed code tile (the ABI packs 32 x 128 codes per tile for every group size G)
 HEAD_DIM = 128    # channels per packed code tile
 
 

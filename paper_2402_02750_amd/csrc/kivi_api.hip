@@ -18,9 +18,9 @@ int check_layout(const kivi_layout_t* l) {
     if (l->decode_path < KIVI_DECODE_AUTO || l->decode_path > KIVI_DECODE_MFMA) return KIVI_ERR_INVALID_ARG;
     if (l->head_dim != kHeadDim) return KIVI_ERR_UNSUPPORTED;
     if (l->bits != 2 && l->bits != 4) return KIVI_ERR_UNSUPPORTED;
-    if (l->group != kTileTokens) return KIVI_ERR_UNSUPPORTED;
+    if (l->group != 32 && l->group != 64 && l->group != 128) return KIVI_ERR_UNSUPPORTED;
     if (l->residual % l->group != 0) return KIVI_ERR_INVALID_ARG;          // Section 3.3: G | R
-    if (l->cap_q_tokens % kTileTokens != 0 || l->cap_r_tokens % kTileTokens != 0) return KIVI_ERR_INVALID_ARG;
+    if (l->cap_q_tokens % l->group != 0 || l->cap_r_tokens % kTileTokens != 0) return KIVI_ERR_INVALID_ARG;
     if (l->cap_r_tokens < l->residual + l->group) return KIVI_ERR_INVALID_ARG;
     const int rep = l->n_q_heads / l->n_kv_heads;
     if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return KIVI_ERR_UNSUPPORTED;
@@ -110,6 +110,7 @@ int enqueue_key_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSo
     p.zero = static_cast<__half*>(c->k_zero);
     p.n_kv_heads = l->n_kv_heads; p.cap_tiles = l->cap_q_tokens / kTileTokens; p.bits = l->bits;
     p.first_tile = c->n_kq / kTileTokens; p.n_tiles = n_tokens / kTileTokens; p.batch = l->batch;
+    p.tiles_per_group = l->group / kTileTokens;
     return hip_status(launch_quantize_keys(p, hs));
 }
 
@@ -122,6 +123,7 @@ int enqueue_value_quant(const kivi_layout_t* l, const kivi_cache_t* c, const Row
     p.zero = static_cast<__half*>(c->v_zero);
     p.n_kv_heads = l->n_kv_heads; p.cap_tiles = l->cap_q_tokens / kTileTokens; p.bits = l->bits;
     p.first_token = c->n_vq; p.n_tokens = n_tokens; p.batch = l->batch;
+    p.group_blocks = l->group / kTileTokens;
     return hip_status(launch_quantize_values(p, hs));
 }
 

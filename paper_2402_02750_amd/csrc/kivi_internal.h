@@ -33,6 +33,7 @@ struct QuantKeyParams {
     int32_t first_tile;   // destination tile index of source token 0
     int32_t n_tiles;
     int32_t batch;
+    int32_t tiles_per_group;   // G / 32: 1, 2 or 4
 };
 
 struct QuantValueParams {
@@ -44,6 +45,7 @@ struct QuantValueParams {
     int32_t first_token;  // destination token index of source token 0 (any value)
     int32_t n_tokens;
     int32_t batch;
+    int32_t group_blocks;      // G / 32: 32-channel blocks per group (1, 2 or 4)
 };
 
 // Copy fp16 rows of every (b, h) from strided tensors into residual rings: up to two (source,

@@ -17,9 +17,9 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ half2v pk_min(half2v a, half2v b) { return __builtin_elementwise_min(a, b); }
 __device__ __forceinline__ half2v pk_max(half2v a, half2v b) { return __builtin_elementwise_max(a, b); }
 
-// consecutive tiles one workgroup walks (measured at the 3968-token prefill of 512 units: keys
-// 165 us with 1, 190 us with 4; values 209 us with 1, 190 us with 4)
-constexpr int kKeyTilesPerGroup = 1, kValueTilesPerGroup = 4;
+// consecutive value tiles one workgroup walks, the next tile's rows prefetched (measured at the
+// 3968-token prefill of 512 units: 209 us with 1, 190 us with 4; the key kernel got slower with it)
+constexpr int kValueTilesPerGroup = 4;
 constexpr int kRowPad = 136;  // halves per LDS row: 272 B keeps 16-byte alignment, skews banks
 
 __device__ __forceinline__ int64_t row_offset(const RowSource& s, int b, int h, int t) {
@@ -76,45 +76,37 @@ __device__ __forceinline__ void word_coords(int wd, int bit, int& lane, int& u, 
     }
 }
 
-template <int BITS>
+// One workgroup quantises one key group: TG tiles of 32 tokens (G = 32 * TG tokens per group).
+// Scale and zero-point rows are stored once per tile, i.e. replicated TG times: the decode kernels
+// read them at tile granularity whatever G is.
+template <int BITS, int TG>
 __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
-    __shared__ __align__(16) __half tile[kTileTokens][kRowPad];
+    constexpr int kRows = TG * kTileTokens;
+    __shared__ __align__(16) __half tile[kRows][kRowPad];
     __shared__ GroupConst sh_g[kHeadDim];
     __shared__ half2v sh_lo[4][kHeadDim / 2], sh_hi[4][kHeadDim / 2];
-    const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     constexpr float levels = (float)((1 << BITS) - 1);
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
-    // This workgroup walks kKeyTilesPerGroup consecutive tiles; the rows of the next tile are
-    // requested into registers before the current one is processed (the per-tile chain of
-    // load -> min/max -> encode is latency-bound otherwise).
-    const int g_lo = blockIdx.x * kKeyTilesPerGroup, g_hi = min(g_lo + kKeyTilesPerGroup, p.n_tiles);
-    uint4 rows[2];
-    auto request = [&](int g) {
-#pragma unroll
-        for (int pass = 0; pass < 2; ++pass) {
-            const int row = pass * 16 + (tid >> 4), seg = tid & 15;
-            rows[pass] = *reinterpret_cast<const uint4*>(
-                p.src.base + row_offset(p.src, b, h, g * kTileTokens + row) + seg * 8);
-        }
-    };
-    request(g_lo);
-    for (int g = g_lo; g < g_hi; ++g) {
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass)
-        *reinterpret_cast<uint4*>(&tile[pass * 16 + (tid >> 4)][(tid & 15) * 8]) = rows[pass];
-    __syncthreads();
-    if (g + 1 < g_hi) request(g + 1);
 
-    const int dst_tile = p.first_tile + g;
-    // Group minimum / maximum with all 256 threads: wavefront w scans tokens 8w..8w+7 of a channel
-    // pair with packed fp16 min / max (exact: no arithmetic), then 128 threads combine the four
-    // partial results of their channel.
+#pragma unroll
+    for (int pass = 0; pass < 2 * TG; ++pass) {
+        const int row = pass * 16 + (tid >> 4), seg = tid & 15;
+        *reinterpret_cast<uint4*>(&tile[row][seg * 8]) = *reinterpret_cast<const uint4*>(
+            p.src.base + row_offset(p.src, b, h, g * kRows + row) + seg * 8);
+    }
+    __syncthreads();
+
+    const int dst_tile = p.first_tile + g * TG;
+    // Group minimum / maximum with all 256 threads: wavefront w scans a quarter of the group's
+    // tokens for a channel pair with packed fp16 min / max (exact: no arithmetic), then 128 threads
+    // combine the four partial results of their channel.
     {
         const int cp = tid & 63, tq = tid >> 6;
-        half2v lo2 = *reinterpret_cast<const half2v*>(&tile[tq * 8][2 * cp]), hi2 = lo2;
+        half2v lo2 = *reinterpret_cast<const half2v*>(&tile[tq * (kRows / 4)][2 * cp]), hi2 = lo2;
 #pragma unroll
-        for (int i = 1; i < 8; ++i) {
-            const half2v x = *reinterpret_cast<const half2v*>(&tile[tq * 8 + i][2 * cp]);
+        for (int i = 1; i < kRows / 4; ++i) {
+            const half2v x = *reinterpret_cast<const half2v*>(&tile[tq * (kRows / 4) + i][2 * cp]);
             lo2 = pk_min(lo2, x);
             hi2 = pk_max(hi2, x);
         }
@@ -132,23 +124,27 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
             hi = fmaxf(hi, __half2float(phi[tq * kHeadDim + tid]));
         }
         const __half s16 = __float2half_rn((hi - lo) / levels);
-        const int64_t o = (unit * p.cap_tiles + dst_tile) * kHeadDim + tid;
-        p.scale[o] = s16;
-        p.zero[o] = __float2half_rn(lo);
+#pragma unroll
+        for (int ti = 0; ti < TG; ++ti) {
+            const int64_t o = (unit * p.cap_tiles + dst_tile + ti) * kHeadDim + tid;
+            p.scale[o] = s16;
+            p.zero[o] = __float2half_rn(lo);
+        }
         sh_g[tid] = group_const(lo, __half2float(s16));
     }
     __syncthreads();
 
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
-    uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;
-    for (int wd = tid; wd < kWords; wd += 256) {
+    uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;     // the TG tiles are consecutive
+    for (int wi = tid; wi < TG * kWords; wi += 256) {
+        const int ti = wi / kWords, wd = wi % kWords;
         uint32_t w = 0;
         bool risky = false;
 #pragma unroll
         for (int bit = 0; bit < 32; bit += BITS) {
             int lane, u, e;
             word_coords<BITS>(wd, bit, lane, u, e);
-            const int t = (u & 1) * 16 + (lane & 15);
+            const int t = ti * kTileTokens + (u & 1) * 16 + (lane & 15);
             const int c = (u >> 1) * 32 + (lane >> 4) * 8 + e;
             w |= encode_fast(__half2float(tile[t][c]), sh_g[c], levels, risky) << bit;
         }
@@ -158,14 +154,12 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
             for (int bit = 0; bit < 32; bit += BITS) {
                 int lane, u, e;
                 word_coords<BITS>(wd, bit, lane, u, e);
-                const int t = (u & 1) * 16 + (lane & 15);
+                const int t = ti * kTileTokens + (u & 1) * 16 + (lane & 15);
                 const int c = (u >> 1) * 32 + (lane >> 4) * 8 + e;
                 w |= encode(__half2float(tile[t][c]), sh_g[c].z, sh_g[c].s, levels) << bit;
             }
         }
-        dst[wd] = w;
-    }
-    __syncthreads();          // the tile and the group constants are overwritten by the next tile
+        dst[wi] = w;
     }
 }
 
@@ -220,6 +214,11 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         float lo = fminf((float)lo2.x, (float)lo2.y), hi = fmaxf((float)hi2.x, (float)hi2.y);
         lo = fminf(lo, __shfl_xor(lo, 1));
         hi = fmaxf(hi, __shfl_xor(hi, 1));
+        // G = 64 or 128 channels per group: combine 2 or 4 neighbouring 32-channel blocks; every
+        // block then stores the group's scale and zero-point (replicated at 32-channel granularity,
+        // which is what the decode kernels read)
+        if (p.group_blocks >= 2) { lo = fminf(lo, __shfl_xor(lo, 2)); hi = fmaxf(hi, __shfl_xor(hi, 2)); }
+        if (p.group_blocks >= 4) { lo = fminf(lo, __shfl_xor(lo, 4)); hi = fmaxf(hi, __shfl_xor(hi, 4)); }
         if (part == 0 && t >= lo_tok && t < hi_tok) {
             const __half s16 = __float2half_rn((hi - lo) / levels);
             const int64_t o = ((unit * p.cap_tiles + dst_tile) * kTileTokens + t) * 4 + cg;
@@ -288,12 +287,21 @@ __global__ __launch_bounds__(256) void copy_rows_kernel(CopyRowsParams p) {
 
 }  // namespace
 
+template <int BITS>
+hipError_t launch_keys_bits(const QuantKeyParams& p, hipStream_t stream) {
+    const int tg = p.tiles_per_group;
+    if (p.n_tiles % tg != 0) return hipErrorInvalidValue;
+    dim3 grid(p.n_tiles / tg, p.n_kv_heads, p.batch), block(256);
+    if (tg == 1) quantize_keys_kernel<BITS, 1><<<grid, block, 0, stream>>>(p);
+    else if (tg == 2) quantize_keys_kernel<BITS, 2><<<grid, block, 0, stream>>>(p);
+    else if (tg == 4) quantize_keys_kernel<BITS, 4><<<grid, block, 0, stream>>>(p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_keys(const QuantKeyParams& p, hipStream_t stream) {
     if (p.n_tiles <= 0) return hipSuccess;
-    dim3 grid((p.n_tiles + kKeyTilesPerGroup - 1) / kKeyTilesPerGroup, p.n_kv_heads, p.batch), block(256);
-    if (p.bits == 2) quantize_keys_kernel<2><<<grid, block, 0, stream>>>(p);
-    else quantize_keys_kernel<4><<<grid, block, 0, stream>>>(p);
-    return hipGetLastError();
+    return p.bits == 2 ? launch_keys_bits<2>(p, stream) : launch_keys_bits<4>(p, stream);
 }
 
 hipError_t launch_quantize_values(const QuantValueParams& p, hipStream_t stream) {

@@ -26,10 +26,10 @@ def gpu_prefill(w, k_np, v_np, policy, decode_path, extra_q_tokens=0):
     """Upload K, V ([b, h, l, 128] fp16 numpy) and run kivi_prefill.  Returns (layout, cache)."""
     import torch
     l = k_np.shape[2]
-    cap_q = max(round_up(l + extra_q_tokens, 32), 32)
+    cap_q = max(round_up(l + extra_q_tokens, w.group), w.group)
     cap_r = round_up(w.residual + w.group, 32) + 32
     layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, cap_q, cap_r,
-                              decode_path=decode_path)
+                              decode_path=decode_path, group=w.group)
     cache = kivi.Cache(layout)
     kt = torch.from_numpy(k_np).cuda()
     vt = torch.from_numpy(v_np).cuda()
@@ -54,11 +54,16 @@ def compare_quantized_state(cache, oc: ko.StreamingCache, heads=None):
         return np.stack([a[b, h] for b, h in heads])[:, None]
 
     nkt, nvt = oc.n_kq // 32, (oc.n_vq + 31) // 32
+    # the library stores scales and zero-points per 32-token tile / 32-channel block whatever G is:
+    # a group of G = 32 * rep_g tokens (channels) has its pair replicated rep_g times
+    rep_g = cache.layout.group // 32
     if nkt:
         got = pick(cache.view("k_codes")[:, :, :nkt]).view(np.uint32)
         assert np.array_equal(got, ko.pack_key_codes(oc.k_codes, bits)), "key codes differ"
-        assert np.array_equal(pick(cache.view("k_scale")[:, :, :nkt]).view(np.uint16), oc.k_scale.view(np.uint16))
-        assert np.array_equal(pick(cache.view("k_zero")[:, :, :nkt]).view(np.uint16), oc.k_zero.view(np.uint16))
+        assert np.array_equal(pick(cache.view("k_scale")[:, :, :nkt]).view(np.uint16),
+                              np.repeat(oc.k_scale, rep_g, axis=2).view(np.uint16))
+        assert np.array_equal(pick(cache.view("k_zero")[:, :, :nkt]).view(np.uint16),
+                              np.repeat(oc.k_zero, rep_g, axis=2).view(np.uint16))
     if oc.n_vq:
         got = pick(cache.view("v_codes")[:, :, :nvt]).view(np.uint32)
         pad = nvt * 32 - oc.n_vq
@@ -69,8 +74,10 @@ def compare_quantized_state(cache, oc: ko.StreamingCache, heads=None):
                                     np.zeros(codes.shape[:2] + (pad, 128), np.uint16)], axis=2)
             got = got & ko.pack_value_codes(valid, bits)
         assert np.array_equal(got, ko.pack_value_codes(codes, bits)), "value codes differ"
-        assert np.array_equal(pick(cache.view("v_scale")[:, :, :oc.n_vq]).view(np.uint16), oc.v_scale.view(np.uint16))
-        assert np.array_equal(pick(cache.view("v_zero")[:, :, :oc.n_vq]).view(np.uint16), oc.v_zero.view(np.uint16))
+        assert np.array_equal(pick(cache.view("v_scale")[:, :, :oc.n_vq]).view(np.uint16),
+                              np.repeat(oc.v_scale, rep_g, axis=3).view(np.uint16))
+        assert np.array_equal(pick(cache.view("v_zero")[:, :, :oc.n_vq]).view(np.uint16),
+                              np.repeat(oc.v_zero, rep_g, axis=3).view(np.uint16))
     for name, start, n, ref in (("k_resid", c.k_r_start, c.n_kr, oc.k_resid),
                                 ("v_resid", c.v_r_start, c.n_vr, oc.v_resid)):
         if n:

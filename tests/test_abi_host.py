@@ -58,7 +58,9 @@ def test_cache_sizes_and_workspace(lib):
 @pytest.mark.parametrize("kw,status", [
     (dict(head_dim=64), kivi.KIVI_ERR_UNSUPPORTED),
     (dict(bits=3), kivi.KIVI_ERR_UNSUPPORTED),
-    (dict(group=64), kivi.KIVI_ERR_UNSUPPORTED),
+    (dict(group=48), kivi.KIVI_ERR_UNSUPPORTED),
+    (dict(group=128, residual=64), kivi.KIVI_ERR_INVALID_ARG),  # G must divide R
+    (dict(group=64, cap_q_tokens=288), kivi.KIVI_ERR_INVALID_ARG),   # capacity in whole groups
     (dict(n_q_heads=3), kivi.KIVI_ERR_INVALID_ARG),
     (dict(residual=48), kivi.KIVI_ERR_INVALID_ARG),           # R must be divisible by G
     (dict(cap_q_tokens=100), kivi.KIVI_ERR_INVALID_ARG),

@@ -78,6 +78,21 @@ def test_alg1_split(path, bits, length):
     _run_case(w, length, kivi.KIVI_FLUSH_ALG1, path)
 
 
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("group,residual,length", [(64, 64, 777), (64, 128, 1500), (128, 128, 1100), (128, 0, 640)])
+def test_larger_groups(path, bits, group, residual, length):
+    """G = 64 and 128 (the group sizes of the paper's ablation, Table 5 / Appendix): keys grouped
+    over G tokens, values over G channels; codes, scales and zero-points bit-exact, outputs in
+    tolerance.  (Scales and zero-points are stored per 32-token tile / 32-channel block, replicated.)"""
+    w = scaled(CONFIGS["llama7b"], name=f"g{group}", batch=2, n_q_heads=2, n_kv_heads=2, bits=bits,
+               group=group, residual=residual, seed=4000 + group + bits)
+    print(f"case group path={path} bits={bits} G={group} R={residual} L={length}", flush=True)
+    _run_case(w, length, kivi.KIVI_FLUSH_WINDOW, path)
+    if residual:
+        _run_case(w, length, kivi.KIVI_FLUSH_ALG1, path)
+
+
 def test_quantize_entry_points_append_in_pieces():
     """kivi_quantize_key_groups / kivi_quantize_value_tokens called piecewise (strided source,
     value pieces that end inside a tile) build the same cache as one call."""

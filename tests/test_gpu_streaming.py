@@ -50,22 +50,24 @@ def test_streaming_small(path, policy, bits):
 
 @pytest.mark.parametrize("path", [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA], ids=["valu", "mfma"])
 @pytest.mark.parametrize("policy", [kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_FLUSH_ALG1], ids=["window", "alg1"])
-@pytest.mark.parametrize("bits,rep", [(2, 1), (4, 2), (2, 4)])
-def test_decode_step_matches_oracle(path, policy, bits, rep):
+@pytest.mark.parametrize("bits,rep,group", [(2, 1, 32), (4, 2, 32), (2, 4, 32), (2, 1, 64), (4, 1, 128)])
+def test_decode_step_matches_oracle(path, policy, bits, rep, group):
     """kivi_decode_step (append + flush + attention, one launch on the steps without a flush in the
     matrix-core family): the residual rings must hold the new token afterwards (bit-exact cache
     at every step that is checked) and the outputs must match at every step."""
     torch = gh.require_gpu()
     w = scaled(CONFIGS["stream"], name="step_small", batch=2, n_q_heads=2 * rep, n_kv_heads=2, bits=bits,
-               residual=64, prompt=101, decode_steps=140, seed=777 + bits + rep)
+               group=group, residual=max(64, group), prompt=101 + 2 * group, decode_steps=140 + group,
+               seed=777 + bits + rep + group)
     total = w.prompt + w.decode_steps
     k, v = workloads.keys(w, total), workloads.values(w, total)
-    print(f"case decode_step path={path} policy={policy} bits={bits} rep={rep}", flush=True)
+    print(f"case decode_step path={path} policy={policy} bits={bits} rep={rep} G={group}", flush=True)
     layout, cache = gh.gpu_prefill(w, k[:, :, :w.prompt], v[:, :, :w.prompt], policy, path,
                                    extra_q_tokens=w.decode_steps)
     oc = ko.StreamingCache(w.batch, w.n_kv_heads, 128, bits, w.group, w.residual,
                            "window" if policy == kivi.KIVI_FLUSH_WINDOW else "alg1")
     oc.prefill(k[:, :, :w.prompt], v[:, :, :w.prompt])
+    gh.compare_quantized_state(cache, oc)
     kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
     worst = 0.0
