@@ -166,9 +166,11 @@ int check_attention_args(const kivi_layout_t* l, const kivi_cache_t* c, const vo
 }
 
 int decode_family(const kivi_layout_t* l) {
-    // the matrix-core family covers up to 4 query heads per kv-head; 8 run on the vector ALUs
+    // the matrix-core family unless the caller asks for the vector ALUs or it has no instantiation
+    // for this (bits, query heads per kv-head)
     const int rep = l->n_q_heads / l->n_kv_heads;
-    return (l->decode_path == KIVI_DECODE_VALU || rep > 4) ? KIVI_DECODE_VALU : KIVI_DECODE_MFMA;
+    if (l->decode_path == KIVI_DECODE_VALU) return KIVI_DECODE_VALU;
+    return mfma_geometry(l->bits, rep).chunk_tiles == 0 ? KIVI_DECODE_VALU : KIVI_DECODE_MFMA;
 }
 
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the

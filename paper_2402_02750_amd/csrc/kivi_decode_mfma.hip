@@ -261,8 +261,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     constexpr int SS = WL::kStageSlots;
     // fp16-row chunks: rows held in registers at once, and whether the first tile's value rows are
     // requested ahead of the logits (both cut for the wider instantiations: register pressure)
-    constexpr int RB = OCC >= 3 ? 4 : 8;
-    constexpr bool kPreloadV = OCC < 3;
+    constexpr int RB = (OCC >= 3 || REP > 4) ? 4 : 8;
+    constexpr bool kPreloadV = OCC < 3 && REP <= 4;
     __shared__ __align__(16) float sm_q[REP][kHeadDim];               // scale * q
     __shared__ __align__(16) __half sm_qf[NC][kKRow];                 // its hi/lo columns (z-term operand)
     __shared__ WL sm_w[4];
@@ -691,17 +691,21 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             softmax_step(cnt);
             wave_lds_sync();
             // ---- phase 3: outputs ----
-            {
-                float racc[REP][8];
+            // (query heads in groups of at most four: with eight the accumulators of the fp16 rows
+            // would not fit in registers; the rows are then loaded once per group)
+            constexpr int HG = REP > 4 ? 4 : REP;
+#pragma unroll 1
+            for (int h0 = 0; h0 < REP; h0 += HG) {
+                float racc[HG][8];
 #pragma unroll
-            for (int hh = 0; hh < REP; ++hh)
+            for (int hh = 0; hh < HG; ++hh)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) racc[hh][e] = 0.f;
             for (int i = 0; i < cnt; ++i) {
                 const int tile = tile0 + wave + 4 * i;
                 const int tt = tile * kTileTokens;
                 const int n_vq_here = min(max(p.n_vq - tt, 0), kTileTokens);
-                if (n_vq_here > 0) {
+                if (n_vq_here > 0 && h0 == 0) {
                     uint32_t w[kLaneWords];
                     load_tile_words<BITS>(p.v_codes + (ubase + wave + 4 * i) * kWords, lane, w);
                     const int64_t so = (ubase + wave + 4 * i) * kTileTokens * 4 + 2 * lane;
@@ -729,8 +733,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                             const int tl = (j0 + j) * 4 + (lane >> 4);
                             const bool use = tl >= n_vq_here && tt + tl < p.length;
 #pragma unroll
-                            for (int hh = 0; hh < REP; ++hh) {
-                                const float pt = use ? wl.lr[2 * hh][i * kTileTokens + tl] : 0.f;
+                            for (int hh = 0; hh < HG; ++hh) {
+                                const float pt = use ? wl.lr[2 * (h0 + hh)][i * kTileTokens + tl] : 0.f;
 #pragma unroll
                                 for (int e = 0; e < 8; ++e) racc[hh][e] = fmaf(pt, (float)vr[j][e], racc[hh][e]);
                             }
@@ -741,7 +745,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             // lane (seg, row) holds channels seg*8.. of every 4th row: add the four row groups into LDS
             wave_lds_sync();
 #pragma unroll
-            for (int hh = 0; hh < REP; ++hh) {
+            for (int hh = 0; hh < HG; ++hh) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     float rr = racc[hh][e];
@@ -749,7 +753,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                     racc[hh][e] = rr;
                 }
                 if (lane < 16) {
-                    float* dst = &sm_r[wave][hh][lane * 8];
+                    float* dst = &sm_r[wave][h0 + hh][lane * 8];
                     float4 a = *reinterpret_cast<float4*>(dst), c = *reinterpret_cast<float4*>(dst + 4);
                     a.x += racc[hh][0]; a.y += racc[hh][1]; a.z += racc[hh][2]; a.w += racc[hh][3];
                     c.x += racc[hh][4]; c.y += racc[hh][5]; c.z += racc[hh][6]; c.w += racc[hh][7];
@@ -887,8 +891,10 @@ bool with_variant(int bits, int rep, F&& fn) {
     if (bits == 2 && rep == 4) { fn(Variant<2, 4, 4, 2>{}); return true; }
     if (bits == 4 && rep == 1) { fn(Variant<4, 1, 4, 2>{}); return true; }
     if (bits == 4 && rep == 2) { fn(Variant<4, 2, 4, 2>{}); return true; }
-    if (bits == 4 && rep == 4) { fn(Variant<4, 4, 4, 2>{}); return true; }
-    return false;                       // 8 query heads per kv-head: vector-ALU family
+    if (bits == 4 && rep == 4) { fn(Variant<4, 4, 2, 2>{}); return true; }
+    if (bits == 2 && rep == 8) { fn(Variant<2, 8, 4, 2>{}); return true; }
+    if (bits == 4 && rep == 8) { fn(Variant<4, 8, 2, 2>{}); return true; }
+    return false;                       // e.g. 4-bit with 8 query heads per kv-head: vector-ALU family
 }
 
 }  // namespace
@@ -903,7 +909,7 @@ hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
 }
 
 MfmaGeometry mfma_geometry(int bits, int rep) {
-    MfmaGeometry g{kMfmaSplitTiles, 512};
+    MfmaGeometry g{0, 0};              // chunk_tiles 0: no matrix-core instantiation for this shape
     with_variant(bits, rep, [&](auto v) {
         using V = decltype(v);
         g.chunk_tiles = 4 * V::slots;

@@ -52,11 +52,16 @@ def test_lengths_and_ragged_tails(path, bits, length):
 
 
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("rep", [2, 4, 8])
-def test_grouped_query(path, rep):
-    w = scaled(CONFIGS["mistral_gqa"], name="gqa_small", batch=2, n_q_heads=2 * rep, n_kv_heads=2, seed=500 + rep)
-    print(f"case gqa path={path} rep={rep}", flush=True)
+def test_grouped_query(path, bits, rep):
+    """2, 4 and 8 query heads per kv-head (8: the 64-query / 8-kv shape of the 70B Llama models);
+    several workgroups per unit, so the cross-workgroup merge runs."""
+    w = scaled(CONFIGS["mistral_gqa"], name="gqa_small", batch=2, n_q_heads=2 * rep, n_kv_heads=2, bits=bits,
+               seed=500 + rep + bits)
+    print(f"case gqa path={path} bits={bits} rep={rep}", flush=True)
     _run_case(w, 1500, kivi.KIVI_FLUSH_WINDOW, path)
+    _run_case(w, 6000, kivi.KIVI_FLUSH_ALG1, path, heads=[(0, 1), (1, 0)])
 
 
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
