@@ -14,17 +14,23 @@
 // exact fp16).  The fp16 residual rows are 5x the bytes per element, so they stay on the vector
 // ALUs.
 //
-// The token axis of every (batch, kv-head) unit is cut into chunks of up to 16 tiles (4 tile slots
-// per wavefront, every 4th tile of the chunk).  The kernel is persistent: the grid is sized to what
-// the chip holds at once and each workgroup (4 wavefronts) walks a contiguous range of chunks.  A
-// wavefront keeps a running softmax maximum and un-normalised output across the chunks of a unit
-// (it rescales only when the maximum grows), and it requests the next chunk's packed data as soon
-// as the registers holding the current chunk's data have been consumed, so HBM requests are in
-// flight all the time -- the scan is latency-bound otherwise.  Chunks whose tiles are all quantised
-// run branch-free (slots past the end of the chunk re-read its last tile and are masked).  When a
-// workgroup leaves a unit it merges its four wavefronts in LDS; if it covered the whole unit it
-// writes the output, otherwise one (m, l, o[128]) per query head goes to the workspace and the
-// last workgroup to finish that unit merges the parts (a counter in the workspace tells which).
+// The token axis of every (batch, kv-head) unit is cut into chunks: all-quantised chunks of 4 * SLOTS
+// tiles (SLOTS tile slots per wavefront, every 4th tile of the chunk) and chunks of up to 16 tiles
+// that hold fp16 rows.  The kernel is persistent: the grid is sized to what the chip holds at once.
+// All chunks lie on one cost axis (unit by unit: its fp16-row chunks, then its all-quantised
+// chunks) that is cut into equal intervals, one per workgroup (4 wavefronts).  A workgroup first
+// walks its fp16-row chunks (phase 1: every row load of a tile issued up front), then its
+// all-quantised chunks (phase 2, software-pipelined: the next chunk's packed data is requested into
+// the registers of the current chunk as soon as a slot has been consumed, so HBM requests are in
+// flight all the time).  The phases are separate because the registers of an in-flight quantised
+// chunk and the row registers / accumulators of phase 1 do not fit side by side.  A wavefront keeps
+// a running softmax maximum and un-normalised output across the chunks of a unit (it rescales only
+// when the maximum grows).  All-quantised chunks run branch-free (slots past the end of the chunk
+// re-read its last tile and are masked).  When a workgroup leaves a unit it merges its four
+// wavefronts in LDS; each (workgroup, phase) that touched the unit contributes one part
+// (m, l, o[128]) per query head to the workspace, and the last contributor to arrive merges the
+// parts (a counter in the workspace tells which).  A workgroup that owns a unit alone carries the
+// unit's state from phase 1 into phase 2 and writes the output directly.
 #include "kivi_internal.h"
 
 #include <hip/hip_fp16.h>
@@ -894,7 +900,7 @@ bool with_variant(int bits, int rep, F&& fn) {
     if (bits == 4 && rep == 4) { fn(Variant<4, 4, 2, 2>{}); return true; }
     if (bits == 2 && rep == 8) { fn(Variant<2, 8, 4, 2>{}); return true; }
     if (bits == 4 && rep == 8) { fn(Variant<4, 8, 2, 2>{}); return true; }
-    return false;                       // e.g. 4-bit with 8 query heads per kv-head: vector-ALU family
+    return false;                       // no instantiation for this shape: the vector-ALU family serves it
 }
 
 }  // namespace
