@@ -39,24 +39,47 @@ __device__ __forceinline__ uint32_t encode(float x, float z, float s, float leve
     return s == 0.0f ? 0u : (uint32_t)r;
 }
 
-// Group constants kept in LDS: zero-point, scale, and the fp32-rounded reciprocal of the scale
-// (0 when the scale is 0, which makes every code of the group 0).
-struct GroupConst { float z, s, y; };
+// Group constants kept in LDS: zero-point and scale (for the exact path), and for the fast path
+// y = fl(1/s), c0 = fl(-z * y) and the tolerance below (y = c0 = 0 when the scale is 0, which
+// makes every code of the group 0).
+struct GroupConst { float z, s, y, c0, tol; };
 
 __device__ __forceinline__ GroupConst group_const(float lo, float s) {
-    return GroupConst{lo, s, s == 0.0f ? 0.0f : 1.0f / s};
+    const float y = s == 0.0f ? 0.0f : 1.0f / s;
+    const float c0 = -lo * y;
+    // q' = fl(x * y + c0) against the contract's q = fl(fl(x - z) / s), with Q the exact quotient:
+    // |q - Q| <= Q * 2^-23 and |q' - Q| <= Q * 2^-23 + |z / s| * 2^-24 * 1.001 (roundings of y, c0 and
+    // of the sum), so for Q <= 16.1:  |q' - q| < 3.9e-6 + |c0| * 6.1e-8.  Twice that as tolerance.
+    return GroupConst{lo, s, y, c0, 8e-6f + fabsf(c0) * 1.3e-7f};
 }
 
-// The same code as encode() without a division per element.  q' = (x - z) * fl(1/s) differs from
-// the correctly rounded quotient q by at most ~2^-22.4 relative (two roundings against one), i.e.
-// by less than 4e-6 for q <= 16, so rint(q') == rint(q) unless q' lies that close to a
-// half-integer.  `risky` is set in that case and the caller redoes the word with encode().
-__device__ __forceinline__ uint32_t encode_fast(float x, const GroupConst& g, float levels, bool& risky) {
-    const float q = (x - g.z) * g.y;
+// The same code as encode() without a division per element: one fused multiply-add straight from
+// the fp16 input.  rint(q') == rint(q) unless q' lies within |q' - q| of a half-integer; `slack`
+// collects the smallest distance to a half-integer over the codes of a word, and the caller redoes
+// the word with encode() when it is below the tolerance.  Returns the clamped code as a float.
+__device__ __forceinline__ float encode_fast(__half x, const GroupConst& g, float levels, float& slack) {
+    const float q = fmaf(__half2float(x), g.y, g.c0);
     const float r = __builtin_rintf(q);
-    risky |= fabsf(fabsf(q - r) - 0.5f) < 2e-5f;
-    return (uint32_t)fminf(fmaxf(r, 0.0f), levels);
+    slack = fminf(slack, fabsf(0.5f - fabsf(q - r)));
+    return fminf(fmaxf(r, 0.0f), levels);
 }
+
+// maximum over the 64 lanes of a wavefront (every lane gets it)
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
+    return v;
+}
+
+// A 32-bit word assembled from float codes: the low and the high 16 bits each stay exact in fp32.
+struct WordAcc {
+    float lo = 0.f, hi = 0.f;
+    __device__ __forceinline__ void add(float code, int bit) {
+        if (bit < 16) lo = fmaf(code, (float)(1u << bit), lo);
+        else hi = fmaf(code, (float)(1u << (bit - 16)), hi);
+    }
+    __device__ __forceinline__ uint32_t word() const { return (uint32_t)lo | ((uint32_t)hi << 16); }
+};
 
 // (u, e) of the code at bit `bit` of word `wd`; lane is implied by wd.
 template <int BITS>
@@ -84,6 +107,7 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
     constexpr int kRows = TG * kTileTokens;
     __shared__ __align__(16) __half tile[kRows][kRowPad];
     __shared__ GroupConst sh_g[kHeadDim];
+    __shared__ float sh_tol[4];         // per wavefront: largest fast-path tolerance of its groups
     __shared__ half2v sh_lo[4][kHeadDim / 2], sh_hi[4][kHeadDim / 2];
     const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     constexpr float levels = (float)((1 << BITS) - 1);
@@ -130,33 +154,60 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
             p.scale[o] = s16;
             p.zero[o] = __float2half_rn(lo);
         }
-        sh_g[tid] = group_const(lo, __half2float(s16));
+        const GroupConst gc = group_const(lo, __half2float(s16));
+        sh_g[tid] = gc;
+        const float wt = wave_max(gc.tol);                    // tid < 128: wavefronts 0 and 1, all lanes active
+        if ((tid & 63) == 0) sh_tol[tid >> 6] = wt;
     }
     __syncthreads();
+    const float tile_tol = fmaxf(sh_tol[0], sh_tol[1]);
 
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
     uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;     // the TG tiles are consecutive
+    // A word of a key tile holds, for two tokens (t0, t0 + 16), a run of 8 (B = 2) or 4 (B = 4)
+    // consecutive channels: read each run from LDS as one vector (2-byte reads of a column of
+    // 16-byte-aligned rows hit only every fourth bank) and the group constants of the run once.
+    constexpr int RUN = 16 / BITS;
     for (int wi = tid; wi < TG * kWords; wi += 256) {
         const int ti = wi / kWords, wd = wi % kWords;
-        uint32_t w = 0;
-        bool risky = false;
-#pragma unroll
-        for (int bit = 0; bit < 32; bit += BITS) {
-            int lane, u, e;
-            word_coords<BITS>(wd, bit, lane, u, e);
-            const int t = ti * kTileTokens + (u & 1) * 16 + (lane & 15);
-            const int c = (u >> 1) * 32 + (lane >> 4) * 8 + e;
-            w |= encode_fast(__half2float(tile[t][c]), sh_g[c], levels, risky) << bit;
+        int lane, c0;
+        if (BITS == 2) {
+            lane = wd >> 2;
+            c0 = (wd & 3) * 32 + (lane >> 4) * 8;
+        } else {
+            lane = (wd & 255) >> 2;
+            const int i = (wd >> 8) * 4 + (wd & 3);
+            c0 = (i >> 1) * 32 + (lane >> 4) * 8 + (i & 1) * 4;
         }
-        if (risky) {          // rare: a quotient next to a rounding tie; redo the word with true divisions
+        const int t0 = ti * kTileTokens + (lane & 15);
+        union Run { uint4 v4; uint2 v2; __half h[8]; } x[2];
+#pragma unroll
+        for (int uo = 0; uo < 2; ++uo) {
+            if (BITS == 2) x[uo].v4 = *reinterpret_cast<const uint4*>(&tile[t0 + uo * 16][c0]);
+            else x[uo].v2 = *reinterpret_cast<const uint2*>(&tile[t0 + uo * 16][c0]);
+        }
+        WordAcc acc;
+        float slack = 1.0f;
+#pragma unroll
+        for (int el = 0; el < RUN; ++el) {
+            const GroupConst gc = sh_g[c0 + el];
+#pragma unroll
+            for (int uo = 0; uo < 2; ++uo) {
+                const int bit = (el & 1) * 16 + (BITS == 2 ? 2 * (uo * 4 + (el >> 1)) : 4 * (uo * 2 + ((el >> 1) & 1)));
+                acc.add(encode_fast(x[uo].h[el], gc, levels, slack), bit);
+            }
+        }
+        uint32_t w = acc.word();
+        if (slack < tile_tol) {     // rare: a quotient next to a rounding tie; redo the word with true divisions
             w = 0;
 #pragma unroll
-            for (int bit = 0; bit < 32; bit += BITS) {
-                int lane, u, e;
-                word_coords<BITS>(wd, bit, lane, u, e);
-                const int t = ti * kTileTokens + (u & 1) * 16 + (lane & 15);
-                const int c = (u >> 1) * 32 + (lane >> 4) * 8 + e;
-                w |= encode(__half2float(tile[t][c]), sh_g[c].z, sh_g[c].s, levels) << bit;
+            for (int el = 0; el < RUN; ++el) {
+                const GroupConst gc = sh_g[c0 + el];
+#pragma unroll
+                for (int uo = 0; uo < 2; ++uo) {
+                    const int bit = (el & 1) * 16 + (BITS == 2 ? 2 * (uo * 4 + (el >> 1)) : 4 * (uo * 2 + ((el >> 1) & 1)));
+                    w |= encode(__half2float(x[uo].h[el]), gc.z, gc.s, levels) << bit;
+                }
             }
         }
         dst[wi] = w;
@@ -167,6 +218,7 @@ template <int BITS>
 __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p) {
     __shared__ __align__(16) __half tile[kTileTokens][kRowPad];
     __shared__ GroupConst sh_g[kTileTokens][4];
+    __shared__ float sh_tol[4];         // per wavefront: largest fast-path tolerance of its groups
     const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     constexpr float levels = (float)((1 << BITS) - 1);
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
@@ -199,6 +251,7 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         *reinterpret_cast<uint4*>(&tile[pass * 16 + (tid >> 4)][(tid & 15) * 8]) = rows[pass];
     __syncthreads();
     if (i + 1 < i_hi) request(i + 1);
+    const bool full = (lo_tok == 0 && hi_tok == kTileTokens);
 
     // Group minimum / maximum with all 256 threads: two threads per (token, channel group), each
     // reduces 16 channels with packed fp16 min / max (exact), partner lanes combine.
@@ -219,34 +272,41 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         // which is what the decode kernels read)
         if (p.group_blocks >= 2) { lo = fminf(lo, __shfl_xor(lo, 2)); hi = fmaxf(hi, __shfl_xor(hi, 2)); }
         if (p.group_blocks >= 4) { lo = fminf(lo, __shfl_xor(lo, 4)); hi = fmaxf(hi, __shfl_xor(hi, 4)); }
+        float my_tol = 0.0f;
         if (part == 0 && t >= lo_tok && t < hi_tok) {
             const __half s16 = __float2half_rn((hi - lo) / levels);
             const int64_t o = ((unit * p.cap_tiles + dst_tile) * kTileTokens + t) * 4 + cg;
             p.scale[o] = s16;
             p.zero[o] = __float2half_rn(lo);
-            sh_g[t][cg] = group_const(lo, __half2float(s16));
+            const GroupConst gc = group_const(lo, __half2float(s16));
+            sh_g[t][cg] = gc;
+            my_tol = gc.tol;
         }
+        const float wt = wave_max(my_tol);
+        if ((tid & 63) == 0) sh_tol[tid >> 6] = wt;
     }
     __syncthreads();
+    const float tile_tol = fmaxf(fmaxf(sh_tol[0], sh_tol[1]), fmaxf(sh_tol[2], sh_tol[3]));
 
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
     uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;
-    const bool full = (lo_tok == 0 && hi_tok == kTileTokens);
     for (int wd = tid; wd < kWords; wd += 256) {
-        uint32_t w = 0, mask = 0;
-        bool risky = false;
+        WordAcc acc;
+        uint32_t mask = 0;
+        float slack = 1.0f;
 #pragma unroll
         for (int bit = 0; bit < 32; bit += BITS) {
             int lane, u, e;
             word_coords<BITS>(wd, bit, lane, u, e);
             const int c = u * 16 + (lane & 15);
             const int t = (lane >> 4) * 8 + e;
-            if (t >= lo_tok && t < hi_tok) {
-                w |= encode_fast(__half2float(tile[t][c]), sh_g[t][c >> 5], levels, risky) << bit;
+            if (full || (t >= lo_tok && t < hi_tok)) {
+                acc.add(encode_fast(tile[t][c], sh_g[t][c >> 5], levels, slack), bit);
                 mask |= (uint32_t)((1 << BITS) - 1) << bit;
             }
         }
-        if (risky) {          // rare: a quotient next to a rounding tie; redo the word with true divisions
+        uint32_t w = acc.word();
+        if (slack < tile_tol) {     // rare: a quotient next to a rounding tie; redo the word with true divisions
             w = 0;
 #pragma unroll
             for (int bit = 0; bit < 32; bit += BITS) {
