@@ -276,6 +276,13 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     __shared__ float sm_zs[4][REP][4];                                // value z-term sums per channel group
     __shared__ float sm_ml[4][REP][2];
     __shared__ int sm_last;
+    // Parts that never leave the workgroup: when this workgroup is the only contributor to a unit in
+    // both phases, the unit's phase-1 result waits here for phase 2 instead of going through the
+    // workspace (no device-scope traffic, no counter).
+    constexpr int kHold = REP <= 2 ? 8 : (REP == 4 ? 4 : 0);
+    __shared__ float sm_hold_o[kHold * REP * kHeadDim + 1];
+    __shared__ float sm_hold_ml[kHold * REP * 2 + 1];
+    __shared__ int sm_hold_unit[kHold + 1];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps tile arithmetic scalar
@@ -382,7 +389,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     };
 
     // ---- leave a unit: merge the four wavefronts, write the output or this workgroup's part ----
-    auto finish_unit = [&](int u, bool fp16_phase, bool sole) {
+    // sole: single part, output written directly; hold_put >= 0: the part is parked in that LDS slot;
+    // hold_get >= 0: the part parked in that slot is merged in and the output written directly.
+    auto finish_unit = [&](int u, bool fp16_phase, bool sole, int hold_put, int hold_get) __attribute__((always_inline)) {
         const int hq0 = (u % p.n_kv_heads) * REP;
         const int b = u / p.n_kv_heads;
         // raw matrix-core outputs: column n of acc[u8] -> lr[n][channel]
@@ -415,7 +424,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         const int g = blockIdx.x;
         int ga0, len_a, gb0, len_b;
         contributors(u, ga0, len_a, gb0, len_b);
-        const int n_parts = sole ? 1 : len_a + len_b;
+        const int n_parts = (sole || hold_put >= 0 || hold_get >= 0) ? 1 : len_a + len_b;
         const int part = fp16_phase ? g - gb0 : len_b + g - ga0;
         const int row_stride = cpu;                               // workspace rows per (batch, query head)
         for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
@@ -436,7 +445,19 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                 }
             }
             const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
-            if (n_parts == 1) {
+            if (hold_put >= 0) {
+                sm_hold_o[(hold_put * REP + hh) * kHeadDim + c] = o;
+                if (c == 0) {
+                    sm_hold_ml[(hold_put * REP + hh) * 2 + 0] = m;
+                    sm_hold_ml[(hold_put * REP + hh) * 2 + 1] = l;
+                }
+            } else if (hold_get >= 0) {
+                const float mh = sm_hold_ml[(hold_get * REP + hh) * 2 + 0], lh = sm_hold_ml[(hold_get * REP + hh) * 2 + 1];
+                const float oh = sm_hold_o[(hold_get * REP + hh) * kHeadDim + c];
+                const float mn = fmaxf(m, mh);                        // at least one of the two is finite
+                const float f_own = __expf(m - mn), f_held = __expf(mh - mn);
+                p.out[row * kHeadDim + c] = fmaf(o, f_own, oh * f_held) / fmaf(l, f_own, lh * f_held);
+            } else if (n_parts == 1) {
                 p.out[row * kHeadDim + c] = o / l;
             } else {
                 // device-scope stores: they go through to memory, no cache flush is needed to publish them
@@ -576,11 +597,22 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             for (int i = 0; i < kSlots; ++i) request_value_slot(i);
         }
     };
+    // A unit's phase-1 part is parked in LDS if this workgroup is the unit's only contributor in both
+    // phases and a slot is free; phase 2 meets the parked units in the same order.
+    int n_held = 0, n_popped = 0;
+    auto finish_fp16_unit = [&](int u) __attribute__((always_inline)) {
+        int ga0, len_a, gb0, len_b;
+        contributors(u, ga0, len_a, gb0, len_b);
+        const bool park = n_held < kHold && len_a == 1 && len_b == 1 && ga0 == (int)blockIdx.x && gb0 == (int)blockIdx.x;
+        if (park && tid == 0) sm_hold_unit[n_held] = u;
+        finish_unit(u, true, false, park ? n_held : -1, -1);
+        n_held += park ? 1 : 0;
+    };
     const int ub_lo = first_b < last_b ? first_b / max(n_b, 1) : 0;
     const int ub_hi = first_b < last_b ? (last_b - 1) / max(n_b, 1) : -1;
     for (int u = ub_lo; u <= ub_hi; ++u) {
         const int b_lo = max(first_b, u * n_b), b_hi = min(last_b, (u + 1) * n_b);
-        if (u > ub_lo) finish_unit(u - 1, true, false);
+        if (u > ub_lo) finish_fp16_unit(u - 1);
         enter_unit(u);
 
         // ---------- chunks that hold fp16 rows ----------
@@ -787,7 +819,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             contributors(ub_hi, ga0, len_a, gb0, len_b);
             carry = len_a == 1 && len_b == 1;
         }
-        if (!carry) finish_unit(ub_hi, true, false);
+        if (!carry) finish_fp16_unit(ub_hi);
     }
     for (int u = ua_lo; u <= ua_hi; ++u) {
         const int a_lo = max(first_a, u * n_a), a_hi = min(last_a, (u + 1) * n_a);
@@ -844,7 +876,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             wave_lds_sync();
         }
 
-        finish_unit(u, false, carried);
+        int get = -1;
+        if (n_popped < n_held && sm_hold_unit[n_popped] == u) get = n_popped++;     // its phase-1 part waits in LDS
+        finish_unit(u, false, carried, -1, get);
     }
 }
 
