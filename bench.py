@@ -230,6 +230,26 @@ def main():
     cold_attn_ms, _ = timed(args.steps, rotate=True, attention_only=True)
     warm_attn_ms, _ = timed(args.steps, rotate=False, attention_only=True)
 
+    # Yardstick: the library's plain read-only stream kernel on this machine -- over as many bytes as
+    # one attention launch moves (rotating over different buffers, so cold like the launches above)
+    # and over 1 GiB (where launch and ramp-up no longer matter).
+    def stream_rate(n_bytes, n_bufs, iters):
+        bufs = [torch.empty(n_bytes, dtype=torch.uint8, device="cuda").fill_(1) for _ in range(n_bufs)]
+        sink = torch.empty(4096, dtype=torch.int32, device="cuda")
+        for i in range(3):
+            kivi.kivi_stream_read_probe(bufs[i % n_bufs], sink, stream)
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        for i in range(iters):
+            kivi.kivi_stream_read_probe(bufs[i % n_bufs], sink, stream)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        return n_bytes / (ev0.elapsed_time(ev1) / iters * 1e-3) / 1e9
+
+    launch_bytes = w.algorithmic_bytes(n_q, n_r)["all"] // 16 * 16
+    stream_same_size = stream_rate(launch_bytes, 5, 200)
+    stream_1gib = stream_rate(1 << 30, 2, 20)
+
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -262,6 +282,9 @@ def main():
             "achieved_packed_only": achieved_packed,
             "frac_packed_only": achieved_packed / HBM_PEAK_GBS,
             "launch_us": cold_attn_ms * 1e3,
+            "stream_read_GBs_same_bytes": stream_same_size,
+            "stream_read_GBs_1GiB": stream_1gib,
+            "frac_of_stream_same_bytes": achieved / stream_same_size,
         },
         "extra": {
             "warm_ms_per_step": warm_step_ms, "warm_attn_us": warm_attn_ms * 1e3,

@@ -213,6 +213,17 @@ int kivi_decode_step(const kivi_layout_t* layout, kivi_cache_t* cache, const voi
                      const void* q, float softmax_scale, int32_t policy, float* out, void* workspace,
                      size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement helper, not part of the method: a plain read-only stream over `bytes` bytes of
+ * device memory (grid-stride 16-byte loads, every workgroup leaves one word in `sink`), the
+ * yardstick the benchmark prices the decode kernel against besides the chip's published HBM peak
+ * (the paper's Section 2 names the once-per-token load of the cache as what bounds decoding).
+ *   src    device, 16-byte aligned, at least `bytes` bytes (a multiple of 16)
+ *   sink   device, at least 4096 * 4 bytes
+ * Errors: INVALID_ARG, HIP.
+ */
+int kivi_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

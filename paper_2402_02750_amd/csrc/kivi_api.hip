@@ -394,4 +394,9 @@ int kivi_decode_step(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new,
     return enqueue_attention(l, c, q, softmax_scale, out, workspace, nullptr, nullptr, stream);
 }
 
+int kivi_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+    if (!src || !sink || !aligned16(src) || !aligned16(sink) || (bytes & 15)) return KIVI_ERR_INVALID_ARG;
+    return hip_status(launch_stream_read(src, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -106,6 +106,7 @@ hipError_t launch_copy_rows(const CopyRowsParams& p, hipStream_t stream);
 hipError_t launch_decode_valu(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_merge(const DecodeParams& p, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
 
 // Chunk length (tiles) of all-quantised chunks and resident workgroups of the matrix-core instantiation
 // that serves (bits, query heads per kv-head); the split planner and the kernel must agree on both.

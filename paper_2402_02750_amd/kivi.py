@@ -26,7 +26,7 @@ KIVI_DECODE_MFMA = 2
 EXPORTS = [
     "kivi_status_string", "kivi_cache_sizes", "kivi_decode_workspace_bytes",
     "kivi_quantize_key_groups", "kivi_quantize_value_tokens", "kivi_prefill", "kivi_append_residual",
-    "kivi_flush_residual", "kivi_decode_attention", "kivi_decode_step",
+    "kivi_flush_residual", "kivi_decode_attention", "kivi_decode_step", "kivi_stream_read_probe",
 ]
 
 
@@ -81,6 +81,7 @@ def load_library() -> ctypes.CDLL:
                                           VP, VP, ctypes.c_size_t, VP]
     lib.kivi_decode_step.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, VP, VP, ctypes.c_float, I32,
                                      VP, VP, ctypes.c_size_t, VP]
+    lib.kivi_stream_read_probe.argtypes = [VP, ctypes.c_size_t, VP, VP]
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -228,3 +229,12 @@ def kivi_decode_step(layout, cache: Cache, k_new, v_new, q_fp16, softmax_scale, 
         ctypes.c_void_p(cache.workspace.data_ptr()), cache.workspace.numel(),
         _stream_handle(stream)), "kivi_decode_step")
     return out_fp32
+
+
+def kivi_stream_read_probe(src, sink, stream=None):
+    """Measurement helper: plain read-only stream over the CUDA tensor `src` (any dtype, contiguous,
+    a multiple of 16 bytes); `sink`: CUDA tensor of at least 16 KiB."""
+    assert src.is_contiguous() and sink.numel() * sink.element_size() >= 4096 * 4
+    _check(load_library().kivi_stream_read_probe(
+        ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(), ctypes.c_void_p(sink.data_ptr()),
+        _stream_handle(stream)), "kivi_stream_read_probe")

@@ -159,3 +159,12 @@ def test_decode_step_validates_before_launch(lib):
     assert call(_fake_cache(n_kq=256, n_kr=95, n_vq=256, n_vr=95)) == kivi.KIVI_ERR_INVALID_ARG
     # WINDOW policy needs the symmetric split
     assert call(_fake_cache(n_kq=64, n_kr=10, n_vq=32, n_vr=42)) == kivi.KIVI_ERR_INVALID_ARG
+
+
+def test_stream_probe_validates(lib):
+    good = ctypes.c_void_p(0x4000)
+    assert lib.kivi_stream_read_probe(None, 1024, good, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert lib.kivi_stream_read_probe(good, 1024, None, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert lib.kivi_stream_read_probe(ctypes.c_void_p(0x4008), 1024, good, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert lib.kivi_stream_read_probe(good, 1000, good, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert lib.kivi_stream_read_probe(good, 0, good, None) == kivi.KIVI_OK          # nothing to read, no launch
