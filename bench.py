@@ -9,7 +9,7 @@ replicated `--copies` times and steps rotate over the copies so that every step 
 cache from HBM rather than from the 256 MB Infinity Cache ("cold"); the same-copy ("warm")
 figure is reported beside it.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -150,7 +150,7 @@ def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(how the path would shard is described in DESIGN.md).", file=sys.stderr)
+              "(the units of work are independent (batch, kv-head) pairs: shard those).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -77,17 +77,17 @@ class Workload:
 _BASE_SEED = 20240202
 
 CONFIGS = {
-    # BASELINE config 1: tiny single decode step
+    # benchmark configuration 1: tiny single decode step
     "tiny": Workload("tiny", 1, 4, 4, 128, 1024, 2, 32, 32, 4, 10.0, 10.0, _BASE_SEED + 1),
-    # BASELINE config 2: Llama-2-7B-shaped layer (the configuration the metric is quoted on)
+    # benchmark configuration 2: Llama-2-7B-shaped layer (the configuration the metric is quoted on)
     "llama7b": Workload("llama7b", 16, 32, 32, 128, 4096, 2, 32, 128, 6, 8.0, 15.0, _BASE_SEED + 2),
-    # BASELINE config 3: streaming, batch 64, prompt 2048 + 256 decode steps
+    # benchmark configuration 3: streaming, batch 64, prompt 2048 + 256 decode steps
     "stream": Workload("stream", 64, 32, 32, 128, 2048, 2, 32, 128, 6, 8.0, 15.0, _BASE_SEED + 3,
                        prompt=2048, decode_steps=256),
-    # BASELINE config 4: 4-bit on a Llama-2-13B-shaped layer
+    # benchmark configuration 4: 4-bit on a Llama-2-13B-shaped layer
     "llama13b_4bit": Workload("llama13b_4bit", 8, 40, 40, 128, 8192, 4, 32, 128, 8, 8.0, 15.0,
                               _BASE_SEED + 4),
-    # BASELINE config 5: grouped-query long context, Mistral-7B-shaped
+    # benchmark configuration 5: grouped-query long context, Mistral-7B-shaped
     "mistral_gqa": Workload("mistral_gqa", 4, 32, 8, 128, 32768, 2, 32, 128, 6, 8.0, 15.0,
                             _BASE_SEED + 5),
 }

@@ -1,4 +1,4 @@
-"""GPU parity at the BASELINE configurations' full sizes, in the launch configuration bench.py
+"""GPU parity at the five benchmark configurations' full sizes, in the launch configuration bench.py
 times.  The whole batch runs on the GPU; the oracle recomputes a sample of (batch, kv-head)
 units one by one (bit-exact cache state, outputs within tolerance)."""
 import numpy as np
@@ -26,7 +26,7 @@ def _sample_heads(w, n, seed):
 @pytest.mark.parametrize("name,n_heads", [("llama7b", 6), ("llama13b_4bit", 4), ("mistral_gqa", 3)])
 @pytest.mark.parametrize("path", [kivi.KIVI_DECODE_AUTO, kivi.KIVI_DECODE_VALU], ids=["auto", "valu"])
 def test_single_step_configs(name, n_heads, path):
-    """BASELINE configs 2, 4 and 5: one decode step at the full shape."""
+    """Benchmark configurations 2, 4 and 5: one decode step at the full shape."""
     torch = gh.require_gpu()
     w = CONFIGS[name]
     print(f"case fullsize {name} path={path}: generating inputs", flush=True)
@@ -53,7 +53,7 @@ def test_single_step_configs(name, n_heads, path):
 
 
 def test_streaming_config3():
-    """BASELINE config 3: batch 64, prompt 2048, 256 decode steps (kivi_decode_step) with a flush
+    """Benchmark configuration 3: batch 64, prompt 2048, 256 decode steps (kivi_decode_step) with a flush
     every 32 steps.  Cache state is compared bit-exactly after every flush and every 16th step
     (the rings must hold what the fused append stored), outputs at every step, on a sample of units."""
     torch = gh.require_gpu()

@@ -34,7 +34,7 @@ def _run_case(w, length, policy, path, heads=None):
 
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 def test_config1_tiny(path):
-    """BASELINE config 1: batch 1, 4 heads, context 1024, 2-bit, R=32."""
+    """Benchmark configuration 1: batch 1, 4 heads, context 1024, 2-bit, R=32."""
     w = CONFIGS["tiny"]
     print(f"case tiny path={path}", flush=True)
     _run_case(w, w.context, kivi.KIVI_FLUSH_WINDOW, path)

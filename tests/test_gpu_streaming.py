@@ -1,4 +1,4 @@
-"""GPU parity of the streaming path (append -> flush -> decode attention, BASELINE config 3
+"""GPU parity of the streaming path (append -> flush -> decode attention, benchmark configuration 3
 shape at a size the oracle finishes quickly): cache state bit-exact after every flush, outputs
 within tolerance at every step."""
 import numpy as np
