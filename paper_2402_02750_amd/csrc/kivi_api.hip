@@ -57,9 +57,12 @@ size_t counter_bytes(const kivi_layout_t* l) {
 }
 
 // Upper bound of the number of context splits for any cache state of this layout.
+// Both planners below give every all-quantised split at least 4 tiles (the matrix-core family 8 or
+// 16), and every split with fp16 rows at least one tile; enqueue_attention checks the actual count
+// against the workspace before it launches.
 int max_splits(const kivi_layout_t* l) {
-    const int tiles = (l->cap_q_tokens + l->cap_r_tokens) / kTileTokens + 1;
-    return tiles;   // every split covers at least one tile
+    const int tiles_q = l->cap_q_tokens / kTileTokens, tiles_r = l->cap_r_tokens / kTileTokens;
+    return (tiles_q + 3) / 4 + tiles_r + 2;
 }
 
 // `mfma`: plan for the persistent matrix-core kernel (fixed chunk length, resident workgroups known);
@@ -176,7 +179,8 @@ int decode_family(const kivi_layout_t* l) {
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the
 // rows of token length-1 are not in the rings yet and the (matrix-core) kernel puts them there.
 int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, float softmax_scale,
-                      float* out, void* workspace, const void* k_new, const void* v_new, void* stream) {
+                      float* out, void* workspace, size_t workspace_bytes, const void* k_new, const void* v_new,
+                      void* stream) {
     const int length = c->n_kq + c->n_kr;
     DecodeParams p{};
     p.k_codes = static_cast<const uint32_t*>(c->k_codes);
@@ -199,6 +203,7 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     p.k_new = static_cast<const __half*>(k_new); p.v_new = static_cast<const __half*>(v_new);
     p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA);
     const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
+    if (counter_bytes(l) + rows * (kHeadDim + 2) * sizeof(float) > workspace_bytes) return KIVI_ERR_WORKSPACE;
     p.counters = static_cast<int32_t*>(workspace);
     p.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + counter_bytes(l));
     p.part_ml = p.part_o + rows * kHeadDim;
@@ -361,7 +366,7 @@ int kivi_decode_attention(const kivi_layout_t* l, const kivi_cache_t* c, const v
     if (int s = check_layout(l)) return s;
     if (int s = check_cache(l, c)) return s;
     if (int s = check_attention_args(l, c, q, out, workspace, workspace_bytes)) return s;
-    return enqueue_attention(l, c, q, softmax_scale, out, workspace, nullptr, nullptr, stream);
+    return enqueue_attention(l, c, q, softmax_scale, out, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
 
 int kivi_decode_step(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new, const void* v_new, const void* q,
@@ -385,13 +390,13 @@ int kivi_decode_step(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new,
         if (int s = check_attention_args(l, &fl, q, out, workspace, workspace_bytes)) return s;
     }
     if (nk == 0 && nv == 0 && decode_family(l) == KIVI_DECODE_MFMA) {
-        if (int s = enqueue_attention(l, &after, q, softmax_scale, out, workspace, k_new, v_new, stream)) return s;
+        if (int s = enqueue_attention(l, &after, q, softmax_scale, out, workspace, workspace_bytes, k_new, v_new, stream)) return s;
         *c = after;
         return KIVI_OK;
     }
     if (int s = kivi_append_residual(l, c, k_new, v_new, stream)) return s;
     if (int s = kivi_flush_residual(l, c, policy, nullptr, nullptr, stream)) return s;
-    return enqueue_attention(l, c, q, softmax_scale, out, workspace, nullptr, nullptr, stream);
+    return enqueue_attention(l, c, q, softmax_scale, out, workspace, workspace_bytes, nullptr, nullptr, stream);
 }
 
 int kivi_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
