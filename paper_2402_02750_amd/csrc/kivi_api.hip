@@ -23,7 +23,7 @@ int check_layout(const kivi_layout_t* l) {
     if (l->cap_q_tokens % l->group != 0 || l->cap_r_tokens % kTileTokens != 0) return KIVI_ERR_INVALID_ARG;
     if (l->cap_r_tokens < l->residual + l->group) return KIVI_ERR_INVALID_ARG;
     const int rep = l->n_q_heads / l->n_kv_heads;
-    if (rep != 1 && rep != 2 && rep != 4 && rep != 8) return KIVI_ERR_UNSUPPORTED;
+    if (rep > kMaxRep) return KIVI_ERR_UNSUPPORTED;
     return KIVI_OK;
 }
 

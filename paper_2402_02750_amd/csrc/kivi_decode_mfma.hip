@@ -292,6 +292,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     constexpr int kLaneWords = BITS * 2;
     WL& wl = sm_w[wave];
 
+    // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
+    // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
+    const int rep = p.n_q_heads / p.n_kv_heads;
     const int n_a = p.plan.n_splits_a, n_b = p.plan.n_splits_b;   // chunks per unit: all-quantised / with fp16 rows
     const int cpu = n_a + n_b;
     // this workgroup's ranges in the two global chunk index spaces (unit-major)
@@ -392,7 +395,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // sole: single part, output written directly; hold_put >= 0: the part is parked in that LDS slot;
     // hold_get >= 0: the part parked in that slot is merged in and the output written directly.
     auto finish_unit = [&](int u, bool fp16_phase, bool sole, int hold_put, int hold_get) __attribute__((always_inline)) {
-        const int hq0 = (u % p.n_kv_heads) * REP;
+        const int hq0 = (u % p.n_kv_heads) * rep;
         const int b = u / p.n_kv_heads;
         // raw matrix-core outputs: column n of acc[u8] -> lr[n][channel]
         if (n < NC) {
@@ -427,7 +430,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         const int n_parts = (sole || hold_put >= 0 || hold_get >= 0) ? 1 : len_a + len_b;
         const int part = fp16_phase ? g - gb0 : len_b + g - ga0;
         const int row_stride = cpu;                               // workspace rows per (batch, query head)
-        for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
+        for (int idx = tid; idx < rep * kHeadDim; idx += 256) {
             const int hh = idx / kHeadDim, c = idx % kHeadDim;
             float m = -INFINITY;
 #pragma unroll
@@ -478,7 +481,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             }
             __syncthreads();
             if (sm_last) {
-                for (int idx = tid; idx < REP * kHeadDim; idx += 256) {
+                for (int idx = tid; idx < rep * kHeadDim; idx += 256) {
                     const int hh = idx / kHeadDim, c = idx % kHeadDim;
                     const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
                     const float* ml = p.part_ml + row * row_stride * 2;
@@ -516,11 +519,11 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 
     // ---- enter a unit: query operands ----
     auto enter_unit = [&](int u) {
-        const int hq0 = (u % p.n_kv_heads) * REP;
+        const int hq0 = (u % p.n_kv_heads) * rep;
         const int b = u / p.n_kv_heads;
         for (int i = tid; i < REP * kHeadDim; i += 256) {
             const int hh = i / kHeadDim, c = i % kHeadDim;
-            const float x = p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]);
+            const float x = hh < rep ? p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f;
             __half hi, lo;
             split_hi_lo(x, hi, lo);
             sm_q[hh][c] = x;
@@ -694,7 +697,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                     // finished logit a is stored as a * 2^-24 in the head's hi column (lo column and
                     // z-term 0), which the softmax turns back into a exactly.
                     const int seg = lane & 15, row = lane >> 4;
-                    const int64_t qrow = ((int64_t)(u / p.n_kv_heads) * p.n_q_heads + (u % p.n_kv_heads) * REP) * kHeadDim;
+                    const int64_t qrow = ((int64_t)(u / p.n_kv_heads) * p.n_q_heads + (u % p.n_kv_heads) * rep) * kHeadDim;
 #pragma unroll
                     for (int j0 = 0; j0 < 8; j0 += RB) {
                         half8 kr[RB];
@@ -708,7 +711,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                         }
 #pragma unroll
                         for (int hh = 0; hh < REP; ++hh) {
-                            const half8 qh = *reinterpret_cast<const half8*>(p.q + qrow + hh * kHeadDim + seg * 8);
+                            const half8 qh = hh < rep ? *reinterpret_cast<const half8*>(p.q + qrow + hh * kHeadDim + seg * 8) : half8{};
 #pragma unroll
                             for (int j = 0; j < RB; ++j) {
                                 const int tl = (j0 + j) * 4 + row;
@@ -925,7 +928,9 @@ template <int B, int R, int S, int O> struct Variant {
     static constexpr int bits = B, rep = R, slots = S, occ = O;
 };
 template <class F>
-bool with_variant(int bits, int rep, F&& fn) {
+bool with_variant(int bits, int rep_layout, F&& fn) {
+    // the smallest instantiation that holds the layout's query heads per kv-head
+    const int rep = rep_layout <= 2 ? rep_layout : (rep_layout <= 4 ? 4 : (rep_layout <= 8 ? 8 : 0));
     if (bits == 2 && rep == 1) { fn(Variant<2, 1, KIVI_V21_SLOTS, KIVI_V21_OCC>{}); return true; }
     if (bits == 2 && rep == 2) { fn(Variant<2, 2, 4, 2>{}); return true; }
     if (bits == 2 && rep == 4) { fn(Variant<2, 4, 4, 2>{}); return true; }

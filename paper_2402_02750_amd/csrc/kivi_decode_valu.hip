@@ -89,11 +89,14 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
     const int n_tiles = tile1 - tile0;
 
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
-    const int hq0 = h * REP;
+    // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
+    // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
+    const int rep = p.n_q_heads / p.n_kv_heads;
+    const int hq0 = h * rep;
 
     for (int i = tid; i < REP * kHeadDim; i += 256) {
         const int hh = i / kHeadDim, c = i % kHeadDim;
-        sm_q[hh][c] = __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]);
+        sm_q[hh][c] = hh < rep ? __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f;
     }
     __syncthreads();
 
@@ -315,6 +318,7 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
             const float* st = stage + ((wv * REP + hh) * 2) * kHeadDim;
             o += st[c] + st[kHeadDim + c];
         }
+        if (hh >= rep) continue;
         const int64_t row = ((int64_t)b * p.n_q_heads + hq0 + hh) * n_splits + split;
         p.part_o[row * kHeadDim + c] = o;
         if (c == 0) {
@@ -347,13 +351,12 @@ template <int BITS>
 hipError_t launch_bits(const DecodeParams& p, hipStream_t stream) {
     const int rep = p.n_q_heads / p.n_kv_heads;
     dim3 grid(p.plan.n_splits(), p.n_kv_heads, p.batch), block(256);
-    switch (rep) {
-        case 1: decode_valu_kernel<BITS, 1><<<grid, block, 0, stream>>>(p); break;
-        case 2: decode_valu_kernel<BITS, 2><<<grid, block, 0, stream>>>(p); break;
-        case 4: decode_valu_kernel<BITS, 4><<<grid, block, 0, stream>>>(p); break;
-        case 8: decode_valu_kernel<BITS, 8><<<grid, block, 0, stream>>>(p); break;
-        default: return hipErrorInvalidValue;
-    }
+    // the smallest instantiation that holds the layout's query heads per kv-head
+    if (rep == 1) decode_valu_kernel<BITS, 1><<<grid, block, 0, stream>>>(p);
+    else if (rep == 2) decode_valu_kernel<BITS, 2><<<grid, block, 0, stream>>>(p);
+    else if (rep <= 4) decode_valu_kernel<BITS, 4><<<grid, block, 0, stream>>>(p);
+    else if (rep <= 8) decode_valu_kernel<BITS, 8><<<grid, block, 0, stream>>>(p);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -53,10 +53,11 @@ def test_lengths_and_ragged_tails(path, bits, length):
 
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("bits", [2, 4])
-@pytest.mark.parametrize("rep", [2, 4, 8])
+@pytest.mark.parametrize("rep", [2, 3, 4, 5, 7, 8])
 def test_grouped_query(path, bits, rep):
-    """2, 4 and 8 query heads per kv-head (8: the 64-query / 8-kv shape of the 70B Llama models);
-    several workgroups per unit, so the cross-workgroup merge runs."""
+    """2 to 8 query heads per kv-head (8: the 64-query / 8-kv shape of the 70B Llama models; 3, 5
+    and 7 run on the next larger instantiation with the surplus heads idle); several workgroups
+    per unit, so the cross-workgroup merge runs."""
     w = scaled(CONFIGS["mistral_gqa"], name="gqa_small", batch=2, n_q_heads=2 * rep, n_kv_heads=2, bits=bits,
                seed=500 + rep + bits)
     print(f"case gqa path={path} bits={bits} rep={rep}", flush=True)
