@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "stream", "llama13b_4bit", "mistral_gqa"])
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--copies", type=int, default=5)
+    ap.add_argument("--cap-pad", type=int, default=1, help="spare 32-token tiles of quantised capacity")
+    ap.add_argument("--skew", type=int, default=None,
+                    help="byte offset between the cache arrays inside their allocations (default: the binding's)")
     ap.add_argument("--context", type=int, default=0, help="override the workload's context length (scaling studies)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -101,7 +104,7 @@ def run_stream(args, w, path_name, path):
     cap_q = (total + 31) // 32 * 32
     layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, cap_q,
                               w.residual + w.group + 32, decode_path=path)
-    cache = kivi.Cache(layout)
+    cache = kivi.Cache(layout, skew=args.skew)
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -175,14 +178,14 @@ def main():
     v = workloads.values(w, L)
     q = workloads.queries(w)
     kt, vt, qt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(q).cuda()
-    cap_q = (n_q + 31) // 32 * 32 + 32
+    cap_q = (n_q + 31) // 32 * 32 + 32 * args.cap_pad
     cap_r = w.residual + w.group + 32
     layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, max(cap_q, 32), cap_r,
                               decode_path=path)
     stream = torch.cuda.current_stream()
 
     # prefill (quantisation) -- timed separately, it is set-up for the decode step
-    caches = [kivi.Cache(layout) for _ in range(max(args.copies, 1))]
+    caches = [kivi.Cache(layout, skew=args.skew) for _ in range(max(args.copies, 1))]
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     kivi.kivi_prefill(layout, kt, vt, L, caches[0])          # warm-up of the quantise kernels
     caches[0].c.n_kq = caches[0].c.n_vq = caches[0].c.n_kr = caches[0].c.n_vr = 0
