@@ -33,10 +33,6 @@
  *   v_codes  uint32 [b][h][cap_q/32][W]   one "value tile" per block of 32 tokens
  *   v_scale  fp16   [b][h][cap_q][4]       per (token, block of 32 channels)
  *   v_zero   fp16   [b][h][cap_q][4]
- *   Placement: any 16-byte-aligned addresses work.  The decode kernel streams tile t of the six
- *   quantised arrays at about the same time, so arrays that share alignment and per-unit stride
- *   meet on the same HBM channels; starting the i-th array i * 8 KB (+ 256 B) into its own
- *   allocation avoids that (up to 10 % of the launch time on a 16 x 32-unit, 4096-token cache).
  *   Scales and zero-points are kept at this 32-token / 32-channel granularity for every G: with
  *   G = 64 or 128 a group's pair is stored in each of the G/32 tiles (blocks) it covers, so the
  *   decode kernels read the same arrays whatever G is (the scale bytes a larger G would save are

@@ -327,19 +327,34 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 
     // The all-quantised chunk whose data is being requested ("next"): unit, chunk index inside the
     // unit, and derived tile range.  Advanced without divisions.
+    // Inside a unit the workgroup's chunks are visited in rotated order, starting at a chunk that
+    // depends on the unit (attention does not care about the order): the workgroups, which run in
+    // lockstep, then read different relative offsets of their units at any one time instead of all
+    // the same one, which keeps their requests from meeting on the same HBM channels whatever the
+    // per-unit stride is.
     int nx_u = 0, nx_j = 0, nx_nt = 1;
+    int nx_lo = 0, nx_len = 1, nx_rot = 0;     // this workgroup's chunk range in unit nx_u, rotation
     bool nx_ok = false;
     int64_t nx_base = 0;
     auto set_next = [&](int ck, bool first_call) {
         nx_ok = ck < last_a;
+        bool new_unit = first_call;
         if (first_call) {
             nx_u = n_a ? ck / n_a : 0;
             nx_j = ck - nx_u * n_a;
         } else if (++nx_j == n_a) {
             nx_j = 0;
             ++nx_u;
+            new_unit = true;
         }
-        const int tile0 = nx_j * p.plan.tiles_per_split_a;
+        if (new_unit) {
+            nx_lo = max(first_a - nx_u * n_a, 0);
+            nx_len = max(min(last_a - nx_u * n_a, n_a) - nx_lo, 1);
+            nx_rot = (nx_u * 3) % nx_len;
+        }
+        int j_phys = nx_j + nx_rot;                          // nx_j runs over [nx_lo, nx_lo + nx_len)
+        j_phys -= j_phys >= nx_lo + nx_len ? nx_len : 0;
+        const int tile0 = j_phys * p.plan.tiles_per_split_a;
         nx_nt = min(p.plan.tiles_per_split_a, p.plan.tiles_a - tile0);
         nx_base = (int64_t)nx_u * p.cap_tiles + tile0;
     };

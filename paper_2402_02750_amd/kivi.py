@@ -133,12 +133,10 @@ class Cache:
 
     _NAMES = ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_resid", "v_resid")
 
-    # Byte offset between the starts of consecutive arrays inside their (2 MB-aligned) allocations.
-    # The decode kernel streams tile t of all six quantised arrays at about the same time; with equal
-    # alignment and equal per-unit strides those streams meet on the same HBM channels.  Measured on
-    # the Llama-2-7B-shaped workload: 48.4-53.0 us per launch over capacities without the offset,
-    # 47.0-49.2 us with 8448 or 12544 bytes.
-    DEFAULT_SKEW = 33 * 256
+    # Optional byte offset between the starts of consecutive arrays inside their allocations (an
+    # experiment knob: the decode kernel visits the chunks of different units in different order, so
+    # its speed no longer depends on how the arrays are placed relative to each other).
+    DEFAULT_SKEW = 0
 
     def __init__(self, layout: kivi_layout_t, device="cuda", skew=None):
         """`skew` (a multiple of 16 bytes, default DEFAULT_SKEW): the i-th array starts i * skew bytes
