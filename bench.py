@@ -29,9 +29,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # scaled by the factor a plain copy kernel of known size reads on the same counters; see the
 # summaries under profiles/.  None until measured for a workload/path.
 MEASURED_TRAFFIC = {
-    # profiles/decode_mfma_llama7b.md: FETCH_SIZE 111969.3 KiB x 2.0 + WRITE_SIZE 387.1 KiB x 1.0
-    ("llama7b", "mfma"): 111969.3 * 1024 * 2.0 + 387.1 * 1024,
-    ("llama7b", "auto"): 111969.3 * 1024 * 2.0 + 387.1 * 1024,
+    # profiles/decode_mfma_llama7b.md: FETCH_SIZE 111996.2 KiB x 2.0 + WRITE_SIZE 387.1 KiB x 1.0
+    ("llama7b", "mfma"): 111996.2 * 1024 * 2.0 + 387.1 * 1024,
+    ("llama7b", "auto"): 111996.2 * 1024 * 2.0 + 387.1 * 1024,
 }
 
 
