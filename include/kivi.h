@@ -17,7 +17,8 @@
  *     including the attention workspace, belong to the caller;
  *   - pointers inside kivi_cache_t, `q`, `out`, `workspace` and the fp16 source tensors are DEVICE
  *     pointers, 16-byte aligned; the structs themselves and all counts live on the host;
- *   - every sequence in the batch has the same length (ragged batches are not supported).
+ *   - the kernels work on batches of equal length; kivi_decode_step_ragged / kivi_decode_attention_ragged
+ *     walk a batch of different lengths in runs of equal length.
  *
  * Arithmetic contract of the quantiser (bit-exact between implementations)
  *   z = min over the group (an fp16 value, stored as is)
@@ -212,6 +213,44 @@ int kivi_decode_attention(const kivi_layout_t* layout, const kivi_cache_t* cache
 int kivi_decode_step(const kivi_layout_t* layout, kivi_cache_t* cache, const void* k_new, const void* v_new,
                      const void* q, float softmax_scale, int32_t policy, float* out, void* workspace,
                      size_t workspace_bytes, void* stream);
+
+/*
+ * Batches whose sequences differ in length.  Entry b of a `kivi_seq_state_t` array (host memory,
+ * one entry per batch entry) holds for sequence b what the integer fields of kivi_cache_t hold for
+ * a batch of equal lengths; the buffers keep the dense [b][h][...] layout with the same capacities
+ * for every sequence.
+ */
+typedef struct kivi_seq_state {
+    int32_t n_kq, n_vq, k_r_start, n_kr, v_r_start, n_vr;
+} kivi_seq_state_t;
+
+/*
+ * Host helper: batch entries [b0, b0 + nb) of `cache` as a cache of their own -- `sub_layout` is
+ * `layout` with batch = nb, `sub_cache` points at the sub-batch's part of every buffer and takes
+ * its integer fields from `state` (from `cache` if `state` is NULL).  Every entry point can then be
+ * used on a part of the batch, e.g. kivi_prefill one sequence at a time.
+ * Errors: INVALID_ARG (range outside the batch, bad layout or cache).
+ */
+int kivi_batch_slice(const kivi_layout_t* layout, const kivi_cache_t* cache, int32_t b0, int32_t nb,
+                     const kivi_seq_state_t* state, kivi_layout_t* sub_layout, kivi_cache_t* sub_cache);
+
+/*
+ * kivi_decode_step / kivi_decode_attention for a batch whose sequences differ in length.  The
+ * integer fields of `cache` are ignored; `states` (host, [batch]) is read and, by the step,
+ * advanced.  The batch is walked in runs of consecutive entries with equal state and each run is
+ * one call of the uniform entry point on that part of the batch (same stream, same workspace): a
+ * batch sorted by length, or one in which many sequences share a length, takes few launches; a
+ * batch of B different lengths takes B.  Entries without any token (all counts 0) are skipped by
+ * kivi_decode_attention_ragged and their `out` rows are left untouched.
+ *   k_new, v_new, q, out   the whole batch's tensors, as for the uniform entry points
+ * Errors: as for the uniform entry points; entries before the failing run have been processed.
+ */
+int kivi_decode_step_ragged(const kivi_layout_t* layout, const kivi_cache_t* cache, kivi_seq_state_t* states,
+                            const void* k_new, const void* v_new, const void* q, float softmax_scale,
+                            int32_t policy, float* out, void* workspace, size_t workspace_bytes, void* stream);
+int kivi_decode_attention_ragged(const kivi_layout_t* layout, const kivi_cache_t* cache,
+                                 const kivi_seq_state_t* states, const void* q, float softmax_scale, float* out,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Measurement helper, not part of the method: a plain read-only stream over `bytes` bytes of

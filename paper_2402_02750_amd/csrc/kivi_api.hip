@@ -218,6 +218,36 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
 
 }  // namespace
 
+namespace {
+
+inline bool same_state(const kivi_seq_state_t& a, const kivi_seq_state_t& b) {
+    return a.n_kq == b.n_kq && a.n_vq == b.n_vq && a.k_r_start == b.k_r_start && a.n_kr == b.n_kr &&
+           a.v_r_start == b.v_r_start && a.n_vr == b.n_vr;
+}
+
+// Walk the batch in runs of equal state; `call(sub_layout, sub_cache, b0)` handles one run and may
+// change the sub-cache's integer fields, which are then written back to the run's states.
+template <class F>
+int for_each_run(const kivi_layout_t* l, const kivi_cache_t* c, kivi_seq_state_t* states, bool write_back, F&& call) {
+    if (int s = check_layout(l)) return s;
+    if (!c || !states) return KIVI_ERR_INVALID_ARG;
+    for (int b0 = 0; b0 < l->batch;) {
+        int b1 = b0 + 1;
+        while (b1 < l->batch && same_state(states[b0], states[b1])) ++b1;
+        kivi_layout_t sl;
+        kivi_cache_t sc;
+        if (int s = kivi_batch_slice(l, c, b0, b1 - b0, &states[b0], &sl, &sc)) return s;
+        if (int s = call(sl, sc, b0)) return s;
+        if (write_back)
+            for (int b = b0; b < b1; ++b)
+                states[b] = kivi_seq_state_t{sc.n_kq, sc.n_vq, sc.k_r_start, sc.n_kr, sc.v_r_start, sc.n_vr};
+        b0 = b1;
+    }
+    return KIVI_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* kivi_status_string(int status) {
@@ -397,6 +427,56 @@ int kivi_decode_step(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new,
     if (int s = kivi_append_residual(l, c, k_new, v_new, stream)) return s;
     if (int s = kivi_flush_residual(l, c, policy, nullptr, nullptr, stream)) return s;
     return enqueue_attention(l, c, q, softmax_scale, out, workspace, workspace_bytes, nullptr, nullptr, stream);
+}
+
+int kivi_batch_slice(const kivi_layout_t* l, const kivi_cache_t* c, int32_t b0, int32_t nb,
+                     const kivi_seq_state_t* state, kivi_layout_t* sub_layout, kivi_cache_t* sub_cache) {
+    if (int s = check_layout(l)) return s;
+    if (!c || !sub_layout || !sub_cache || b0 < 0 || nb < 1 || (int64_t)b0 + nb > l->batch) return KIVI_ERR_INVALID_ARG;
+    kivi_cache_sizes_t sz;
+    if (int s = kivi_cache_sizes(l, &sz)) return s;
+    *sub_layout = *l;
+    sub_layout->batch = nb;
+    *sub_cache = *c;
+    // every array is dense [b][h][...]: one sequence takes 1/batch of it
+    auto move = [&](void* base, size_t total) -> void* {
+        return base ? static_cast<char*>(base) + total / l->batch * b0 : nullptr;
+    };
+    sub_cache->k_codes = move(c->k_codes, sz.k_codes); sub_cache->k_scale = move(c->k_scale, sz.k_scale);
+    sub_cache->k_zero = move(c->k_zero, sz.k_zero);    sub_cache->v_codes = move(c->v_codes, sz.v_codes);
+    sub_cache->v_scale = move(c->v_scale, sz.v_scale); sub_cache->v_zero = move(c->v_zero, sz.v_zero);
+    sub_cache->k_resid = move(c->k_resid, sz.k_resid); sub_cache->v_resid = move(c->v_resid, sz.v_resid);
+    if (state) {
+        sub_cache->n_kq = state->n_kq; sub_cache->n_vq = state->n_vq; sub_cache->k_r_start = state->k_r_start;
+        sub_cache->n_kr = state->n_kr; sub_cache->v_r_start = state->v_r_start; sub_cache->n_vr = state->n_vr;
+    }
+    return check_cache(sub_layout, sub_cache);
+}
+
+int kivi_decode_step_ragged(const kivi_layout_t* l, const kivi_cache_t* c, kivi_seq_state_t* states,
+                            const void* k_new, const void* v_new, const void* q, float softmax_scale,
+                            int32_t policy, float* out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!k_new || !v_new || !q || !out) return KIVI_ERR_INVALID_ARG;
+    return for_each_run(l, c, states, true, [&](kivi_layout_t& sl, kivi_cache_t& sc, int b0) {
+        const size_t kv_row = (size_t)l->n_kv_heads * kHeadDim, q_row = (size_t)l->n_q_heads * kHeadDim;
+        return kivi_decode_step(&sl, &sc, static_cast<const __half*>(k_new) + b0 * kv_row,
+                                static_cast<const __half*>(v_new) + b0 * kv_row,
+                                static_cast<const __half*>(q) + b0 * q_row, softmax_scale, policy,
+                                out + b0 * q_row, workspace, workspace_bytes, stream);
+    });
+}
+
+int kivi_decode_attention_ragged(const kivi_layout_t* l, const kivi_cache_t* c, const kivi_seq_state_t* states,
+                                 const void* q, float softmax_scale, float* out, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (!q || !out) return KIVI_ERR_INVALID_ARG;
+    return for_each_run(l, c, const_cast<kivi_seq_state_t*>(states), false,
+                        [&](kivi_layout_t& sl, kivi_cache_t& sc, int b0) {
+        if (sc.n_kq + sc.n_kr == 0 && sc.n_vq + sc.n_vr == 0) return (int)KIVI_OK;      // empty slots of the batch
+        const size_t q_row = (size_t)l->n_q_heads * kHeadDim;
+        return kivi_decode_attention(&sl, &sc, static_cast<const __half*>(q) + b0 * q_row, softmax_scale,
+                                     out + b0 * q_row, workspace, workspace_bytes, stream);
+    });
 }
 
 int kivi_stream_read_probe(const void* src, size_t bytes, void* sink, void* stream) {

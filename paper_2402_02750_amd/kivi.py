@@ -27,6 +27,7 @@ EXPORTS = [
     "kivi_status_string", "kivi_cache_sizes", "kivi_decode_workspace_bytes",
     "kivi_quantize_key_groups", "kivi_quantize_value_tokens", "kivi_prefill", "kivi_append_residual",
     "kivi_flush_residual", "kivi_decode_attention", "kivi_decode_step", "kivi_stream_read_probe",
+    "kivi_batch_slice", "kivi_decode_step_ragged", "kivi_decode_attention_ragged",
 ]
 
 
@@ -46,6 +47,10 @@ class kivi_cache_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in (
         "k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_resid", "v_resid")] + \
         [(n, ctypes.c_int32) for n in ("n_kq", "n_vq", "k_r_start", "n_kr", "v_r_start", "n_vr")]
+
+
+class kivi_seq_state_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_kq", "n_vq", "k_r_start", "n_kr", "v_r_start", "n_vr")]
 
 
 class kivi_cache_sizes_t(ctypes.Structure):
@@ -82,6 +87,12 @@ def load_library() -> ctypes.CDLL:
     lib.kivi_decode_step.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, VP, VP, ctypes.c_float, I32,
                                      VP, VP, ctypes.c_size_t, VP]
     lib.kivi_stream_read_probe.argtypes = [VP, ctypes.c_size_t, VP, VP]
+    lib.kivi_batch_slice.argtypes = [P(kivi_layout_t), P(kivi_cache_t), I32, I32, P(kivi_seq_state_t),
+                                     P(kivi_layout_t), P(kivi_cache_t)]
+    lib.kivi_decode_step_ragged.argtypes = [P(kivi_layout_t), P(kivi_cache_t), P(kivi_seq_state_t), VP, VP, VP,
+                                            ctypes.c_float, I32, VP, VP, ctypes.c_size_t, VP]
+    lib.kivi_decode_attention_ragged.argtypes = [P(kivi_layout_t), P(kivi_cache_t), P(kivi_seq_state_t), VP,
+                                                 ctypes.c_float, VP, VP, ctypes.c_size_t, VP]
     for name in EXPORTS[1:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -248,3 +259,48 @@ def kivi_stream_read_probe(src, sink, stream=None):
     _check(load_library().kivi_stream_read_probe(
         ctypes.c_void_p(src.data_ptr()), src.numel() * src.element_size(), ctypes.c_void_p(sink.data_ptr()),
         _stream_handle(stream)), "kivi_stream_read_probe")
+
+
+class CacheSlice:
+    """Batch entries [b0, b0 + nb) of a Cache as a cache of their own (kivi_batch_slice): `layout`
+    and `c` can be passed to every entry point, e.g. to prefill one sequence of a ragged batch."""
+
+    def __init__(self, cache: Cache, b0: int, nb: int, state=None):
+        self.parent = cache
+        self.layout = kivi_layout_t()
+        self.c = kivi_cache_t()
+        self.workspace = cache.workspace
+        _check(load_library().kivi_batch_slice(
+            ctypes.byref(cache.layout), ctypes.byref(cache.c), b0, nb,
+            ctypes.byref(state) if state is not None else None,
+            ctypes.byref(self.layout), ctypes.byref(self.c)), "kivi_batch_slice")
+
+    def state(self) -> kivi_seq_state_t:
+        return kivi_seq_state_t(self.c.n_kq, self.c.n_vq, self.c.k_r_start, self.c.n_kr, self.c.v_r_start, self.c.n_vr)
+
+
+def make_states(batch: int):
+    """Host array of per-sequence states (all empty) for the ragged entry points."""
+    return (kivi_seq_state_t * batch)()
+
+
+def kivi_decode_step_ragged(layout, cache: Cache, states, k_new, v_new, q_fp16, softmax_scale, out_fp32,
+                            policy=KIVI_FLUSH_WINDOW, stream=None):
+    """kivi_decode_step over a batch whose sequences differ in length; `states` from make_states."""
+    assert k_new.is_contiguous() and v_new.is_contiguous() and q_fp16.is_contiguous() and out_fp32.is_contiguous()
+    _check(load_library().kivi_decode_step_ragged(
+        ctypes.byref(layout), ctypes.byref(cache.c), states, ctypes.c_void_p(k_new.data_ptr()),
+        ctypes.c_void_p(v_new.data_ptr()), ctypes.c_void_p(q_fp16.data_ptr()), ctypes.c_float(softmax_scale),
+        policy, ctypes.c_void_p(out_fp32.data_ptr()), ctypes.c_void_p(cache.workspace.data_ptr()),
+        cache.workspace.numel(), _stream_handle(stream)), "kivi_decode_step_ragged")
+    return out_fp32
+
+
+def kivi_decode_attention_ragged(layout, cache: Cache, states, q_fp16, softmax_scale, out_fp32, stream=None):
+    assert q_fp16.is_contiguous() and out_fp32.is_contiguous()
+    _check(load_library().kivi_decode_attention_ragged(
+        ctypes.byref(layout), ctypes.byref(cache.c), states, ctypes.c_void_p(q_fp16.data_ptr()),
+        ctypes.c_float(softmax_scale), ctypes.c_void_p(out_fp32.data_ptr()),
+        ctypes.c_void_p(cache.workspace.data_ptr()), cache.workspace.numel(), _stream_handle(stream)),
+        "kivi_decode_attention_ragged")
+    return out_fp32

@@ -48,10 +48,10 @@ def compare_quantized_state(cache, oc: ko.StreamingCache, heads=None):
     cap_r = cache.layout.cap_r_tokens
 
     def pick(t):
-        a = t.cpu().numpy()
         if heads is None:
-            return a
-        return np.stack([a[b, h] for b, h in heads])[:, None]
+            return t.cpu().numpy()
+        # slice on the device: at full sizes the arrays hold gigabytes
+        return torch.stack([t[b, h] for b, h in heads])[:, None].cpu().numpy()
 
     nkt, nvt = oc.n_kq // 32, (oc.n_vq + 31) // 32
     # the library stores scales and zero-points per 32-token tile / 32-channel block whatever G is:

@@ -169,3 +169,45 @@ def test_stream_probe_validates(lib):
     assert lib.kivi_stream_read_probe(ctypes.c_void_p(0x4008), 1024, good, None) == kivi.KIVI_ERR_INVALID_ARG
     assert lib.kivi_stream_read_probe(good, 1000, good, None) == kivi.KIVI_ERR_INVALID_ARG
     assert lib.kivi_stream_read_probe(good, 0, good, None) == kivi.KIVI_OK          # nothing to read, no launch
+
+
+def test_batch_slice_and_ragged_validate(lib):
+    l = _layout()
+    c = _fake_cache(n_kq=64, n_kr=3, n_vq=64, n_vr=3)
+    sl, sc = kivi.kivi_layout_t(), kivi.kivi_cache_t()
+    f = lib.kivi_batch_slice
+    assert f(ctypes.byref(l), ctypes.byref(c), -1, 1, None, ctypes.byref(sl), ctypes.byref(sc)) == kivi.KIVI_ERR_INVALID_ARG
+    assert f(ctypes.byref(l), ctypes.byref(c), 0, 0, None, ctypes.byref(sl), ctypes.byref(sc)) == kivi.KIVI_ERR_INVALID_ARG
+    assert f(ctypes.byref(l), ctypes.byref(c), l.batch - 1, 2, None, ctypes.byref(sl), ctypes.byref(sc)) == kivi.KIVI_ERR_INVALID_ARG
+    assert f(ctypes.byref(l), ctypes.byref(c), 0, 1, None, None, ctypes.byref(sc)) == kivi.KIVI_ERR_INVALID_ARG
+    # a state that does not fit the layout is refused
+    bad = kivi.kivi_seq_state_t(n_kq=33, n_vq=32, n_kr=1, n_vr=2)
+    assert f(ctypes.byref(l), ctypes.byref(c), 0, 1, ctypes.byref(bad), ctypes.byref(sl), ctypes.byref(sc)) == kivi.KIVI_ERR_INVALID_ARG
+    # the slice: same geometry, batch nb, every array moved by b0 sequences, counters from `state`
+    sizes = kivi.kivi_cache_sizes_t()
+    assert lib.kivi_cache_sizes(ctypes.byref(l), ctypes.byref(sizes)) == kivi.KIVI_OK
+    st = kivi.kivi_seq_state_t(n_kq=32, n_vq=32, k_r_start=5, n_kr=7, v_r_start=5, n_vr=7)
+    b0 = l.batch - 1
+    assert f(ctypes.byref(l), ctypes.byref(c), b0, 1, ctypes.byref(st), ctypes.byref(sl), ctypes.byref(sc)) == kivi.KIVI_OK
+    assert (sl.batch, sl.n_kv_heads, sl.bits, sl.cap_q_tokens, sl.cap_r_tokens) == (
+        1, l.n_kv_heads, l.bits, l.cap_q_tokens, l.cap_r_tokens)
+    for name in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_resid", "v_resid"):
+        assert getattr(sc, name) - getattr(c, name) == getattr(sizes, name) // l.batch * b0, name
+    assert (sc.n_kq, sc.n_vq, sc.k_r_start, sc.n_kr, sc.v_r_start, sc.n_vr) == (32, 32, 5, 7, 5, 7)
+
+    good = ctypes.c_void_p(0x2000)
+    out = ctypes.c_void_p(0x3000)
+    states = kivi.make_states(l.batch)
+    step, att = lib.kivi_decode_step_ragged, lib.kivi_decode_attention_ragged
+    assert step(ctypes.byref(l), ctypes.byref(c), None, good, good, good, 0.1, 0, out, good, 1 << 30, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert step(ctypes.byref(l), ctypes.byref(c), states, None, good, good, 0.1, 0, out, good, 1 << 30, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert att(ctypes.byref(l), ctypes.byref(c), None, good, 0.1, out, good, 1 << 30, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert att(ctypes.byref(l), ctypes.byref(c), states, None, 0.1, out, good, 1 << 30, None) == kivi.KIVI_ERR_INVALID_ARG
+    # all slots empty: nothing to attend to, no launch
+    assert att(ctypes.byref(l), ctypes.byref(c), states, good, 0.1, out, good, 1 << 30, None) == kivi.KIVI_OK
+    # a full ring in one sequence is refused before anything is launched, states unchanged
+    for b in range(l.batch):
+        states[b] = kivi.kivi_seq_state_t(n_kq=64, n_vq=64, n_kr=96, n_vr=96)
+    before = bytes(states)
+    assert step(ctypes.byref(l), ctypes.byref(c), states, good, good, good, 0.1, 0, out, good, 1 << 30, None) == kivi.KIVI_ERR_INVALID_ARG
+    assert bytes(states) == before

@@ -91,3 +91,50 @@ def test_streaming_config3():
             print(f"case stream: step {step} ok, worst abs err so far {worst:.3e}", flush=True)
     assert flushes == [32, 64, 96, 128, 160, 192, 224, 256]
     assert (cache.c.n_kq, cache.c.n_kr) == (2176, 128)
+
+
+def test_arrays_beyond_4GiB():
+    """Maximum sizes: packed code arrays of 4.36 GB each and fp16 prefill inputs of 17.5 GB each, so
+    that byte and element offsets pass 2^31 and 2^32 inside every kernel.  Inputs are drawn on the
+    device (seeded torch generator, the workload's outlier-channel gains applied) because the host
+    generator would need minutes; the sampled units' rows are copied back for the oracle.  Units
+    0, 64 (beyond 2 GiB) and 127 (beyond 4 GiB) are compared bit-exactly and on their outputs."""
+    torch = gh.require_gpu()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 80e9:
+        pytest.skip("needs 80 GB of free device memory")
+    w = workloads.scaled(CONFIGS["llama13b_4bit"], name="beyond4g", batch=16, n_q_heads=8, n_kv_heads=8,
+                         context=520 * 1024 + 128, seed=4242)
+    T = w.context
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    gain = torch.from_numpy(np.stack([workloads.channel_gain(w, h) for h in range(w.n_kv_heads)])).cuda()
+    print("case beyond4g: generating inputs on the device", flush=True)
+    kt = torch.empty(w.batch, w.n_kv_heads, T, 128, dtype=torch.float16, device="cuda")
+    vt = torch.empty_like(kt)
+    for b in range(w.batch):
+        kt[b] = (torch.randn(w.n_kv_heads, T, 128, generator=gen, device="cuda") * gain[:, None, :]).half()
+        vt[b] = torch.randn(w.n_kv_heads, T, 128, generator=gen, device="cuda").half()
+    heads = [(0, 0), (8, 0), (15, 7)]
+    k_s = torch.stack([kt[b, h] for b, h in heads])[:, None].cpu().numpy()
+    v_s = torch.stack([vt[b, h] for b, h in heads])[:, None].cpu().numpy()
+    n_q, n_r = w.split_single_step()
+    print("case beyond4g: oracle prefill of 3 units", flush=True)
+    oc = ko.StreamingCache(len(heads), 1, 128, w.bits, w.group, w.residual, "window")
+    oc.prefill(k_s, v_s)
+    q = workloads.queries(w)
+    ref = gh.oracle_attention_for_heads(w, oc, q, heads)
+    for path in (kivi.KIVI_DECODE_AUTO, kivi.KIVI_DECODE_VALU):
+        print(f"case beyond4g: path {path}", flush=True)
+        layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, gh.round_up(T, 32), 192,
+                                  decode_path=path)
+        cache = kivi.Cache(layout)
+        assert cache.buffers["k_codes"].numel() * cache.buffers["k_codes"].element_size() > 2 ** 32
+        kivi.kivi_prefill(layout, kt, vt, T, cache, kivi.KIVI_FLUSH_WINDOW)
+        torch.cuda.synchronize()
+        assert (cache.c.n_kq, cache.c.n_kr) == (n_q, n_r)
+        gh.compare_quantized_state(cache, oc, heads)
+        out = gh.gpu_attention(layout, cache, q, w.softmax_scale)
+        assert np.isfinite(out).all()
+        err = gh.check_close(gh.pick_heads(out, w, heads), ref, f"beyond4g path {path}")
+        print(f"case beyond4g: path {path} max abs err {err:.3e}", flush=True)
+        del cache

@@ -1,0 +1,83 @@
+"""Batches whose sequences differ in length: per-sequence prefill through kivi_batch_slice, then
+decoding steps through kivi_decode_step_ragged; every sequence against an oracle cache of its own
+(bit-exact state, outputs within tolerance)."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import gpu_harness as gh
+from oracle import kivi_oracle as ko
+from paper_2402_02750_amd import kivi, workloads
+from paper_2402_02750_amd.workloads import CONFIGS, scaled
+
+pytestmark = pytest.mark.gpu
+
+
+class _SeqView:
+    """Duck-typed stand-in for kivi.Cache over one sequence, for gh.compare_quantized_state."""
+
+    def __init__(self, cache, b, state):
+        self.cache, self.b, self.layout = cache, b, cache.layout
+        self.c = state
+
+    def view(self, name):
+        return self.cache.view(name)[self.b:self.b + 1]
+
+
+@pytest.mark.parametrize("path", [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA], ids=["valu", "mfma"])
+@pytest.mark.parametrize("policy", [kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_FLUSH_ALG1], ids=["window", "alg1"])
+def test_ragged_batch_steps(path, policy):
+    torch = gh.require_gpu()
+    prompts = [300, 300, 37, 1500, 0, 801]          # two equal neighbours, a short one, an empty slot
+    steps = 70
+    w = scaled(CONFIGS["stream"], name="ragged", batch=len(prompts), n_q_heads=4, n_kv_heads=2, residual=64,
+               prompt=0, decode_steps=0, seed=606)
+    total = max(prompts) + steps
+    k, v = workloads.keys(w, total), workloads.values(w, total)
+    layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, gh.round_up(total, 32), 128,
+                              decode_path=path)
+    cache = kivi.Cache(layout)
+    states = kivi.make_states(w.batch)
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    pol = "window" if policy == kivi.KIVI_FLUSH_WINDOW else "alg1"
+    oracles = []
+    print(f"case ragged path={path} policy={policy}: per-sequence prefill", flush=True)
+    for b, n in enumerate(prompts):
+        oc = ko.StreamingCache(1, w.n_kv_heads, 128, w.bits, w.group, w.residual, pol)
+        if n:
+            sl = kivi.CacheSlice(cache, b, 1)
+            kivi.kivi_prefill(sl.layout, kt[b:b + 1], vt[b:b + 1], n, sl, policy)
+            states[b] = sl.state()
+            oc.prefill(k[b:b + 1, :, :n], v[b:b + 1, :, :n])
+        oracles.append(oc)
+    out = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    lengths = list(prompts)
+    for step in range(steps):
+        q = workloads.queries(w, step)
+        # every sequence appends the token at its own position
+        k_new = torch.stack([kt[b, :, lengths[b]] for b in range(w.batch)]).contiguous()
+        v_new = torch.stack([vt[b, :, lengths[b]] for b in range(w.batch)]).contiguous()
+        kivi.kivi_decode_step_ragged(layout, cache, states, k_new, v_new, torch.from_numpy(q).cuda(),
+                                     w.softmax_scale, out, policy)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        for b in range(w.batch):
+            oc = oracles[b]
+            oc.append(k[b:b + 1, :, lengths[b]], v[b:b + 1, :, lengths[b]])
+            lengths[b] += 1
+            st = states[b]
+            assert (st.n_kq, st.n_kr, st.n_vq, st.n_vr) == (oc.n_kq, oc.n_kr, oc.n_vq, oc.n_vr), f"step {step} seq {b}"
+            gh.check_close(got[b:b + 1], oc.attention(q[b:b + 1], w.softmax_scale), f"step {step} seq {b}")
+            if step % 16 == 15:
+                gh.compare_quantized_state(_SeqView(cache, b, st), oc)
+    # attention only, with one slot emptied: its rows of `out` stay as they are
+    states[2] = kivi.kivi_seq_state_t()
+    out.fill_(7.0)
+    q = workloads.queries(w, steps)
+    kivi.kivi_decode_attention_ragged(layout, cache, states, torch.from_numpy(q).cuda(), w.softmax_scale, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert (got[2] == 7.0).all()
+    for b in (0, 1, 3, 4, 5):
+        gh.check_close(got[b:b + 1], oracles[b].attention(q[b:b + 1], w.softmax_scale), f"final seq {b}")
