@@ -83,7 +83,9 @@ extern "C" {
 /* Static description of one attention layer's cache (host struct). */
 typedef struct kivi_layout {
     int32_t batch;          /* b                                                          */
-    int32_t n_q_heads;      /* query heads; a multiple (1x to 8x) of n_kv_heads           */
+    int32_t n_q_heads;      /* query heads; a multiple (1x to 128x) of n_kv_heads: up to  */
+                            /* 8 query heads per kv-head share one pass over the cache,   */
+                            /* wider groups (multi-query attention) take one pass per 8   */
     int32_t n_kv_heads;     /* key/value heads                                            */
     int32_t head_dim;       /* D; this build supports 128                                 */
     int32_t bits;           /* B: 2 or 4                                                  */

@@ -23,7 +23,7 @@ int check_layout(const kivi_layout_t* l) {
     if (l->cap_q_tokens % l->group != 0 || l->cap_r_tokens % kTileTokens != 0) return KIVI_ERR_INVALID_ARG;
     if (l->cap_r_tokens < l->residual + l->group) return KIVI_ERR_INVALID_ARG;
     const int rep = l->n_q_heads / l->n_kv_heads;
-    if (rep > kMaxRep) return KIVI_ERR_UNSUPPORTED;
+    if (rep > kMaxRepTotal) return KIVI_ERR_UNSUPPORTED;
     return KIVI_OK;
 }
 
@@ -73,7 +73,7 @@ SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, bool mfma) 
     s.tiles_a = std::min(c->n_kq, c->n_vq) / kTileTokens;
     s.tiles_total = ceil_div(length, kTileTokens);
     const int64_t units = (int64_t)l->batch * l->n_kv_heads;
-    const int rep = l->n_q_heads / l->n_kv_heads;
+    const int rep = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);      // heads per launch (wider groups: several launches)
     const int tiles_b = s.tiles_total - s.tiles_a;
     int tps_b_max;
     if (mfma) {
@@ -171,7 +171,7 @@ int check_attention_args(const kivi_layout_t* l, const kivi_cache_t* c, const vo
 int decode_family(const kivi_layout_t* l) {
     // the matrix-core family unless the caller asks for the vector ALUs or it has no instantiation
     // for this (bits, query heads per kv-head)
-    const int rep = l->n_q_heads / l->n_kv_heads;
+    const int rep = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
     if (l->decode_path == KIVI_DECODE_VALU) return KIVI_DECODE_VALU;
     return mfma_geometry(l->bits, rep).chunk_tiles == 0 ? KIVI_DECODE_VALU : KIVI_DECODE_MFMA;
 }
@@ -209,9 +209,20 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     p.part_ml = p.part_o + rows * kHeadDim;
 
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    hipError_t e = path == KIVI_DECODE_MFMA ? launch_decode_mfma(p, hs) : launch_decode_valu(p, hs);
-    if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
-    if (int s = hip_status(e)) return s;
+    // Up to kMaxRep query heads per kv-head go through one launch.  A wider group (multi-query
+    // attention: 71 heads on one kv-head) takes one launch per kMaxRep heads, each reading the cache
+    // again; the launches share the plan and the workspace (their part rows are disjoint, and the
+    // matrix-core kernel leaves its counters at zero).  Only the first one appends the new token.
+    const int rep_total = l->n_q_heads / l->n_kv_heads;
+    p.rep_variant = std::min(rep_total, kMaxRep);
+    for (int h0 = 0; h0 < rep_total; h0 += kMaxRep) {
+        p.q_head0 = h0;
+        p.rep_here = std::min(kMaxRep, rep_total - h0);
+        hipError_t e = path == KIVI_DECODE_MFMA ? launch_decode_mfma(p, hs) : launch_decode_valu(p, hs);
+        if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
+        if (int s = hip_status(e)) return s;
+        p.k_new = p.v_new = nullptr;
+    }
     // the matrix-core kernel merges its splits itself; the vector-ALU family uses a second launch
     return path == KIVI_DECODE_MFMA ? KIVI_OK : hip_status(launch_merge(p, hs));
 }

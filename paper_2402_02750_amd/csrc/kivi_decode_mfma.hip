@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 
     // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
     // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
-    const int rep = p.n_q_heads / p.n_kv_heads;
+    const int rep = p.rep_here, rep_total = p.n_q_heads / p.n_kv_heads;
     const int n_a = p.plan.n_splits_a, n_b = p.plan.n_splits_b;   // chunks per unit: all-quantised / with fp16 rows
     const int cpu = n_a + n_b;
     // this workgroup's ranges in the two global chunk index spaces (unit-major)
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // sole: single part, output written directly; hold_put >= 0: the part is parked in that LDS slot;
     // hold_get >= 0: the part parked in that slot is merged in and the output written directly.
     auto finish_unit = [&](int u, bool fp16_phase, bool sole, int hold_put, int hold_get) __attribute__((always_inline)) {
-        const int hq0 = (u % p.n_kv_heads) * rep;
+        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
         const int b = u / p.n_kv_heads;
         // raw matrix-core outputs: column n of acc[u8] -> lr[n][channel]
         if (n < NC) {
@@ -534,7 +534,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 
     // ---- enter a unit: query operands ----
     auto enter_unit = [&](int u) {
-        const int hq0 = (u % p.n_kv_heads) * rep;
+        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
         const int b = u / p.n_kv_heads;
         for (int i = tid; i < REP * kHeadDim; i += 256) {
             const int hh = i / kHeadDim, c = i % kHeadDim;
@@ -712,7 +712,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                     // finished logit a is stored as a * 2^-24 in the head's hi column (lo column and
                     // z-term 0), which the softmax turns back into a exactly.
                     const int seg = lane & 15, row = lane >> 4;
-                    const int64_t qrow = ((int64_t)(u / p.n_kv_heads) * p.n_q_heads + (u % p.n_kv_heads) * rep) * kHeadDim;
+                    const int64_t qrow = ((int64_t)(u / p.n_kv_heads) * p.n_q_heads + (u % p.n_kv_heads) * rep_total + p.q_head0) * kHeadDim;
 #pragma unroll
                     for (int j0 = 0; j0 < 8; j0 += RB) {
                         half8 kr[RB];
@@ -961,7 +961,7 @@ bool with_variant(int bits, int rep_layout, F&& fn) {
 
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
-    with_variant(p.bits, p.n_q_heads / p.n_kv_heads, [&](auto v) {
+    with_variant(p.bits, p.rep_variant, [&](auto v) {
         using V = decltype(v);
         e = launch_one<V::bits, V::rep, V::slots, V::occ>(p, stream);
     });

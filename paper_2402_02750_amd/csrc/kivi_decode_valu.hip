@@ -91,8 +91,8 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
     // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
     // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
-    const int rep = p.n_q_heads / p.n_kv_heads;
-    const int hq0 = h * rep;
+    const int rep = p.rep_here;
+    const int hq0 = h * (p.n_q_heads / p.n_kv_heads) + p.q_head0;
 
     for (int i = tid; i < REP * kHeadDim; i += 256) {
         const int hh = i / kHeadDim, c = i % kHeadDim;
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(128) void merge_kernel(DecodeParams p) {
 
 template <int BITS>
 hipError_t launch_bits(const DecodeParams& p, hipStream_t stream) {
-    const int rep = p.n_q_heads / p.n_kv_heads;
+    const int rep = p.rep_variant;
     dim3 grid(p.plan.n_splits(), p.n_kv_heads, p.batch), block(256);
     // the smallest instantiation that holds the layout's query heads per kv-head
     if (rep == 1) decode_valu_kernel<BITS, 1><<<grid, block, 0, stream>>>(p);

@@ -14,7 +14,8 @@ constexpr int kHeadDim = 128;
 constexpr int kTileTokens = 32;        // tokens per code tile == supported group size G
 constexpr int kMaxSplitTiles = 32;     // a context split covers at most 32 tiles (1024 tokens)
 constexpr int kMfmaSplitTiles = 16;    // ... at most 16 tiles in the matrix-core family (4 per wavefront)
-constexpr int kMaxRep = 8;             // query heads per kv-head handled by one workgroup pass
+constexpr int kMaxRep = 8;             // query heads per kv-head handled by one launch
+constexpr int kMaxRepTotal = 128;      // query heads per kv-head of a layout (wider groups take several launches)
 
 // Source of fp16 rows for the quantise kernels: either a strided tensor or a ring buffer.
 struct RowSource {
@@ -90,6 +91,11 @@ struct DecodeParams {
     float* part_o;          // workspace: [b][H_q][n_splits][128]
     float softmax_scale;
     int32_t batch, n_q_heads, n_kv_heads, bits, length;
+    // One launch serves query heads [q_head0, q_head0 + rep_here) of every kv-head's group, on the
+    // kernel instantiation for rep_variant heads (>= rep_here; the surplus heads idle).  A group of
+    // up to kMaxRep heads is one launch; a wider one (multi-query attention) takes several, all on
+    // the kMaxRep instantiation so that they share one split plan.
+    int32_t q_head0, rep_here, rep_variant;
     SplitPlan plan;
     // Persistent matrix-core kernel.  Work lies on a cost axis: unit u occupies [u * cost_unit,
     // (u + 1) * cost_unit): first its fp16-row chunks (cost_b each), then its all-quantised chunks

@@ -62,7 +62,7 @@ def test_cache_sizes_and_workspace(lib):
     (dict(group=128, residual=64), kivi.KIVI_ERR_INVALID_ARG),  # G must divide R
     (dict(group=64, cap_q_tokens=288), kivi.KIVI_ERR_INVALID_ARG),   # capacity in whole groups
     (dict(n_q_heads=3), kivi.KIVI_ERR_INVALID_ARG),
-    (dict(n_q_heads=32), kivi.KIVI_ERR_UNSUPPORTED),              # 16 query heads per kv-head
+    (dict(n_q_heads=258), kivi.KIVI_ERR_UNSUPPORTED),             # 129 query heads per kv-head (limit 128)
     (dict(residual=48), kivi.KIVI_ERR_INVALID_ARG),           # R must be divisible by G
     (dict(cap_q_tokens=100), kivi.KIVI_ERR_INVALID_ARG),
     (dict(cap_r_tokens=64), kivi.KIVI_ERR_INVALID_ARG),       # needs R + G

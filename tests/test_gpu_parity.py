@@ -66,6 +66,20 @@ def test_grouped_query(path, bits, rep):
 
 
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("n_kv,rep", [(2, 9), (2, 16), (1, 71)])
+def test_wide_groups(path, bits, n_kv, rep):
+    """More than 8 query heads per kv-head: one pass over the cache per 8 heads (9 = 8 + 1, 16 = two
+    full passes, 71 heads on a single kv-head = the multi-query shape of Falcon-7B, 8 passes of 8
+    and one of 7)."""
+    w = scaled(CONFIGS["mistral_gqa"], name="wide", batch=2, n_q_heads=n_kv * rep, n_kv_heads=n_kv, bits=bits,
+               seed=1500 + rep + bits)
+    print(f"case wide path={path} bits={bits} kv={n_kv} rep={rep}", flush=True)
+    _run_case(w, 1500, kivi.KIVI_FLUSH_WINDOW, path)
+    _run_case(w, 3100, kivi.KIVI_FLUSH_ALG1, path)
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("residual", [0, 32, 96])
 def test_residual_lengths(path, residual):
     w = scaled(CONFIGS["llama7b"], name="resid", batch=1, n_q_heads=2, n_kv_heads=2, residual=residual, seed=900)
