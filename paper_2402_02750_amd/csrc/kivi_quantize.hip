@@ -50,18 +50,23 @@ __device__ __forceinline__ GroupConst group_const(float lo, float s) {
     // q' = fl(x * y + c0) against the contract's q = fl(fl(x - z) / s), with Q the exact quotient:
     // |q - Q| <= Q * 2^-23 and |q' - Q| <= Q * 2^-23 + |z / s| * 2^-24 * 1.001 (roundings of y, c0 and
     // of the sum), so for Q <= 16.1:  |q' - q| < 3.9e-6 + |c0| * 6.1e-8.  Twice that as tolerance.
-    return GroupConst{lo, s, y, c0, 8e-6f + fabsf(c0) * 1.3e-7f};
+    // (scale below the smallest normal fp16 number: its rounding error is not relative, the quotient
+    // can pass `levels`: tolerance 1 = always the exact path)
+    return GroupConst{lo, s, y, c0, (s != 0.0f && s < 6.103515625e-05f) ? 1.0f : 8e-6f + fabsf(c0) * 1.3e-7f};
 }
 
 // The same code as encode() without a division per element: one fused multiply-add straight from
-// the fp16 input.  rint(q') == rint(q) unless q' lies within |q' - q| of a half-integer; `slack`
-// collects the smallest distance to a half-integer over the codes of a word, and the caller redoes
-// the word with encode() when it is below the tolerance.  Returns the clamped code as a float.
-__device__ __forceinline__ float encode_fast(__half x, const GroupConst& g, float levels, float& slack) {
+// the fp16 input.  rint(q') == rint(q) unless q' lies within |q' - q| of a half-integer; `dev`
+// collects the largest distance |q' - rint(q')| over the codes of a word, and the caller redoes the
+// word with encode() when it exceeds 0.5 - tolerance.  No clamp: x >= z keeps the quotient at or
+// above -tolerance, and with a normal fp16 scale s >= (max - min) / levels * (1 - 2^-11) it stays
+// below levels + 0.008; a group whose scale is an fp16 subnormal gets a tolerance that sends its
+// tile down the exact path (group_const).  Returns the code as a float.
+__device__ __forceinline__ float encode_fast(__half x, const GroupConst& g, float& dev) {
     const float q = fmaf(__half2float(x), g.y, g.c0);
     const float r = __builtin_rintf(q);
-    slack = fminf(slack, fabsf(0.5f - fabsf(q - r)));
-    return fminf(fmaxf(r, 0.0f), levels);
+    dev = fmaxf(dev, fabsf(q - r));
+    return r;
 }
 
 // maximum over the 64 lanes of a wavefront (every lane gets it)
@@ -187,18 +192,18 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
             else x[uo].v2 = *reinterpret_cast<const uint2*>(&tile[t0 + uo * 16][c0]);
         }
         WordAcc acc;
-        float slack = 1.0f;
+        float dev = 0.0f;
 #pragma unroll
         for (int el = 0; el < RUN; ++el) {
             const GroupConst gc = sh_g[c0 + el];
 #pragma unroll
             for (int uo = 0; uo < 2; ++uo) {
                 const int bit = (el & 1) * 16 + (BITS == 2 ? 2 * (uo * 4 + (el >> 1)) : 4 * (uo * 2 + ((el >> 1) & 1)));
-                acc.add(encode_fast(x[uo].h[el], gc, levels, slack), bit);
+                acc.add(encode_fast(x[uo].h[el], gc, dev), bit);
             }
         }
         uint32_t w = acc.word();
-        if (slack < tile_tol) {     // rare: a quotient next to a rounding tie; redo the word with true divisions
+        if (dev > 0.5f - tile_tol) {     // rare: a quotient next to a rounding tie; redo the word with true divisions
             w = 0;
 #pragma unroll
             for (int el = 0; el < RUN; ++el) {
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
     for (int wd = tid; wd < kWords; wd += 256) {
         WordAcc acc;
         uint32_t mask = 0;
-        float slack = 1.0f;
+        float dev = 0.0f;
 #pragma unroll
         for (int bit = 0; bit < 32; bit += BITS) {
             int lane, u, e;
@@ -301,12 +306,12 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
             const int c = u * 16 + (lane & 15);
             const int t = (lane >> 4) * 8 + e;
             if (full || (t >= lo_tok && t < hi_tok)) {
-                acc.add(encode_fast(tile[t][c], sh_g[t][c >> 5], levels, slack), bit);
+                acc.add(encode_fast(tile[t][c], sh_g[t][c >> 5], dev), bit);
                 mask |= (uint32_t)((1 << BITS) - 1) << bit;
             }
         }
         uint32_t w = acc.word();
-        if (slack < tile_tol) {     // rare: a quotient next to a rounding tie; redo the word with true divisions
+        if (dev > 0.5f - tile_tol) {     // rare: a quotient next to a rounding tie; redo the word with true divisions
             w = 0;
 #pragma unroll
             for (int bit = 0; bit < 32; bit += BITS) {
