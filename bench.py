@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--copies", type=int, default=5)
     ap.add_argument("--cap-pad", type=int, default=1, help="spare 32-token tiles of quantised capacity")
+    ap.add_argument("--cap-r-pad", type=int, default=0, help="spare 32-token tiles of residual-ring capacity")
     ap.add_argument("--skew", type=int, default=None,
                     help="byte offset between the cache arrays inside their allocations (default: the binding's)")
     ap.add_argument("--context", type=int, default=0, help="override the workload's context length (scaling studies)")
@@ -103,7 +104,7 @@ def run_stream(args, w, path_name, path):
     v_new = [vt[:, :, w.prompt + s].contiguous() for s in range(w.decode_steps)]
     cap_q = (total + 31) // 32 * 32
     layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, cap_q,
-                              w.residual + w.group + 32, decode_path=path)
+                              w.residual + w.group + 32 + 32 * args.cap_r_pad, decode_path=path)
     cache = kivi.Cache(layout, skew=args.skew)
     out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
@@ -179,7 +180,7 @@ def main():
     q = workloads.queries(w)
     kt, vt, qt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), torch.from_numpy(q).cuda()
     cap_q = (n_q + 31) // 32 * 32 + 32 * args.cap_pad
-    cap_r = w.residual + w.group + 32
+    cap_r = w.residual + w.group + 32 + 32 * args.cap_r_pad
     layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, max(cap_q, 32), cap_r,
                               decode_path=path)
     stream = torch.cuda.current_stream()
