@@ -42,7 +42,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=500,
                     help="untimed steps; a few hundred let the clocks settle (a step is ~50 us)")
     ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "stream", "llama13b_4bit", "mistral_gqa"])
-    ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma", "mfma1", "mfma2"])
     ap.add_argument("--copies", type=int, default=5)
     ap.add_argument("--cap-pad", type=int, default=1, help="spare 32-token tiles of quantised capacity")
     ap.add_argument("--cap-r-pad", type=int, default=0, help="spare 32-token tiles of residual-ring capacity")
@@ -166,14 +166,16 @@ def main():
     torch.cuda.set_device(0)
     w = workloads.CONFIGS[args.workload]
     if w.decode_steps:
-        path = {"auto": kivi.KIVI_DECODE_AUTO, "valu": kivi.KIVI_DECODE_VALU, "mfma": kivi.KIVI_DECODE_MFMA}[args.path]
+        path = {"auto": kivi.KIVI_DECODE_AUTO, "valu": kivi.KIVI_DECODE_VALU, "mfma": kivi.KIVI_DECODE_MFMA,
+            "mfma1": kivi.KIVI_DECODE_MFMA_ONE, "mfma2": kivi.KIVI_DECODE_MFMA_TWO}[args.path]
         print(json.dumps(run_stream(args, w, args.path, path)))
         return
     if args.context:
         w = workloads.scaled(w, name=f"{w.name}@{args.context}", context=args.context)
     n_q, n_r = w.split_single_step()
     L = w.context
-    path = {"auto": kivi.KIVI_DECODE_AUTO, "valu": kivi.KIVI_DECODE_VALU, "mfma": kivi.KIVI_DECODE_MFMA}[args.path]
+    path = {"auto": kivi.KIVI_DECODE_AUTO, "valu": kivi.KIVI_DECODE_VALU, "mfma": kivi.KIVI_DECODE_MFMA,
+            "mfma1": kivi.KIVI_DECODE_MFMA_ONE, "mfma2": kivi.KIVI_DECODE_MFMA_TWO}[args.path]
 
     k = workloads.keys(w, L)
     v = workloads.values(w, L)

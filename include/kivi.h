@@ -79,6 +79,11 @@ extern "C" {
 #define KIVI_DECODE_AUTO        0
 #define KIVI_DECODE_VALU        1   /* vector-ALU dot products + cross-lane reductions               */
 #define KIVI_DECODE_MFMA        2   /* codes fed to the matrix cores as exact fp16                   */
+#define KIVI_DECODE_MFMA_ONE    3   /* ... always as one launch                                      */
+#define KIVI_DECODE_MFMA_TWO    4   /* ... as two launches where the cache has both quantised tokens */
+                                    /* and fp16 rows: the fp16 rows first, then the quantised part   */
+                                    /* (KIVI_DECODE_MFMA and AUTO take two launches when a workgroup */
+                                    /* would otherwise own several (batch, kv-head) units)           */
 
 /* Static description of one attention layer's cache (host struct). */
 typedef struct kivi_layout {

@@ -12,7 +12,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libkivi_hip.so")
 
-SOURCES = ["kivi_api.hip", "kivi_quantize.hip", "kivi_decode_valu.hip", "kivi_decode_mfma.hip"]
+SOURCES = ["kivi_api.hip", "kivi_quantize.hip", "kivi_decode_valu.hip", "kivi_decode_mfma.hip",
+           "kivi_decode_rows.hip"]
 
 COMMON_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -15,7 +15,7 @@ int check_layout(const kivi_layout_t* l) {
     if (l->batch > 65535 || l->n_kv_heads > 65535) return KIVI_ERR_INVALID_ARG;
     if (l->n_q_heads % l->n_kv_heads != 0) return KIVI_ERR_INVALID_ARG;
     if (l->residual < 0 || l->cap_q_tokens < 0 || l->cap_r_tokens < 0) return KIVI_ERR_INVALID_ARG;
-    if (l->decode_path < KIVI_DECODE_AUTO || l->decode_path > KIVI_DECODE_MFMA) return KIVI_ERR_INVALID_ARG;
+    if (l->decode_path < KIVI_DECODE_AUTO || l->decode_path > KIVI_DECODE_MFMA_TWO) return KIVI_ERR_INVALID_ARG;
     if (l->head_dim != kHeadDim) return KIVI_ERR_UNSUPPORTED;
     if (l->bits != 2 && l->bits != 4) return KIVI_ERR_UNSUPPORTED;
     if (l->group != 32 && l->group != 64 && l->group != 128) return KIVI_ERR_UNSUPPORTED;
@@ -67,7 +67,8 @@ int max_splits(const kivi_layout_t* l) {
 
 // `mfma`: plan for the persistent matrix-core kernel (fixed chunk length, resident workgroups known);
 // otherwise for the vector-ALU family.
-SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, bool mfma) {
+// `two_launches` (matrix-core family only): a single fp16-row split per unit, served by a launch of its own.
+SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, bool mfma, bool two_launches = false) {
     SplitPlan s{};
     const int length = c->n_kq + c->n_kr;
     s.tiles_a = std::min(c->n_kq, c->n_vq) / kTileTokens;
@@ -83,6 +84,7 @@ SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, bool mfma) 
         const MfmaGeometry g = mfma_geometry(l->bits, rep);
         s.tiles_per_split_a = g.chunk_tiles;
         tps_b_max = (int)std::max<int64_t>(1, std::min<int64_t>(4, units * tiles_b / g.resident_workgroups));
+        if (two_launches) tps_b_max = std::max(tiles_b, 1);
     } else {
         // Aim at ~16 workgroups per compute unit in flight over the whole grid so the 256 CUs stay
         // busy through the tail, but keep splits long enough that the per-split partial results
@@ -201,7 +203,24 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     const int path = decode_family(l);
     if ((k_new || v_new) && path != KIVI_DECODE_MFMA) return KIVI_ERR_UNSUPPORTED;
     p.k_new = static_cast<const __half*>(k_new); p.v_new = static_cast<const __half*>(v_new);
-    p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA);
+    // The matrix-core family as two launches (fp16 rows first, then the all-quantised chunks): possible
+    // when the cache has both parts and K and V are split at the same token; chosen when asked for,
+    // or when a workgroup of the persistent kernel would own several (batch, kv-head) units -- their
+    // fp16-row chunks would then run one after the other, each a chain of dependent steps.
+    bool two = false;
+    if (path == KIVI_DECODE_MFMA && l->decode_path != KIVI_DECODE_MFMA_ONE) {
+        const int rep_launch = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
+        const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
+        const int tiles_b = ceil_div(c->n_kq + c->n_kr, kTileTokens) - c->n_kq / kTileTokens;
+        const bool possible = c->n_kq == c->n_vq && c->n_kq >= kTileTokens && c->n_kr > 0 &&
+                              residual_rows_possible(tiles_b, rep_variant);
+        const int64_t units = (int64_t)l->batch * l->n_kv_heads;
+        const int resident = mfma_geometry(l->bits, std::min(l->n_q_heads / l->n_kv_heads, kMaxRep)).resident_workgroups;
+        // (measured at 32 heads, context 4096, 2 bits: equal at 1 unit per workgroup, 4-6 % faster from 1.5 on)
+        two = possible && (l->decode_path == KIVI_DECODE_MFMA_TWO || units * 4 >= (int64_t)resident * 5);
+    }
+    p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
+    p.two_launches = two ? 1 : 0;
     const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
     if (counter_bytes(l) + rows * (kHeadDim + 2) * sizeof(float) > workspace_bytes) return KIVI_ERR_WORKSPACE;
     p.counters = static_cast<int32_t*>(workspace);

@@ -42,6 +42,7 @@
 #define KIVI_V21_OCC 2
 #endif
 
+
 namespace kivi {
 namespace {
 
@@ -70,6 +71,14 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global load of the wavefront, i.e. for the next chunk's data requested ahead.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // data-parallel-primitive lane moves (all source lanes are valid for these patterns)
@@ -257,7 +266,14 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
 
 // SLOTS: tile slots per wavefront of an all-quantised chunk (chunk = 4 * SLOTS tiles); OCC: workgroups
 // per compute unit the register budget is sized for.
-template <int BITS, int REP, int SLOTS, int OCC>
+// MODE: kBothPhases = the whole attention in one launch.  When a workgroup would own several units
+// the fp16 rows are served by a launch of their own (residual_rows_kernel: one wavefront per tile,
+// many wavefronts per compute unit, one part per tile in the workspace) and this kernel follows as
+// kQuantisedOnly: the all-quantised chunks only; whoever finishes a unit merges the parts of the
+// first launch into it.
+constexpr int kBothPhases = 0, kQuantisedOnly = 1;
+
+template <int BITS, int REP, int SLOTS, int OCC, int MODE>
 __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     constexpr int kSlots = SLOTS;
     // tile slots staged at once: two where that divides the slots and the registers allow
@@ -295,8 +311,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
     // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
     const int rep = p.rep_here, rep_total = p.n_q_heads / p.n_kv_heads;
-    const int n_a = p.plan.n_splits_a, n_b = p.plan.n_splits_b;   // chunks per unit: all-quantised / with fp16 rows
-    const int cpu = n_a + n_b;
+    // chunks per unit on this launch's cost axis: all-quantised / with fp16 rows
+    const int n_a = p.plan.n_splits_a, n_b = MODE == kQuantisedOnly ? 0 : p.plan.n_splits_b;
+    const int cpu = p.plan.n_splits_a + p.plan.n_splits_b;       // workspace rows per (batch, query head)
     // this workgroup's ranges in the two global chunk index spaces (unit-major)
     // Index arithmetic on the cost axis; 32-bit whenever the products fit (64-bit division costs
     // more than a hundred instructions each and every workgroup does about a dozen).
@@ -404,6 +421,48 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         len_b = n_b ? owner(base + (n_b - 1) * cost_b) - gb0 + 1 : 0;
         ga0 = n_a ? owner(a0) : 0;
         len_a = n_a ? owner(a0 + n_a - 1) - ga0 + 1 : 0;
+        if (MODE == kQuantisedOnly) {       // the parts the fp16-row launch left for the unit: one per tile
+            gb0 = 0;
+            len_b = p.plan.n_splits_b;
+        }
+    };
+
+    // kQuantisedOnly: part 0 of the current unit (what the fp16-row launch left), requested when the
+    // unit is entered so that it has arrived long before the unit is left (with eight heads, for want
+    // of registers, only when the unit is left); thread tid holds the values of its elements
+    // idx = tid + 256 k of finish_unit's loop.
+    constexpr int kIdx = (REP * kHeadDim + 255) / 256;
+    constexpr bool kPrefetchPart = REP <= 4;
+    // kQuantisedOnly also requests the next unit's query one unit ahead and separates the units with
+    // LDS-only barriers: the next chunk's data, in flight when a unit is left, then keeps travelling
+    // while the workgroup merges, writes the output and stages the next query.  (kBothPhases keeps
+    // __syncthreads(): its launches have one unit per workgroup where this would matter.)
+    auto unit_barrier = [&]() {
+        if constexpr (MODE == kQuantisedOnly) lds_barrier();
+        else __syncthreads();
+    };
+    __half q_pre[kIdx];
+    auto request_q = [&](int u) {
+        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
+        const int b = u / p.n_kv_heads;
+#pragma unroll
+        for (int k = 0; k < kIdx; ++k) {
+            const int idx = min(tid + 256 * k, rep * kHeadDim - 1);        // unconditional loads (clamped)
+            q_pre[k] = p.q[((int64_t)b * p.n_q_heads + hq0 + idx / kHeadDim) * kHeadDim + idx % kHeadDim];
+        }
+    };
+    float pre_m[kIdx], pre_l[kIdx], pre_o[kIdx];
+    auto request_rows_part = [&](int u) {
+        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
+        const int b = u / p.n_kv_heads;
+#pragma unroll
+        for (int k = 0; k < kIdx; ++k) {
+            const int idx = min(tid + 256 * k, rep * kHeadDim - 1);        // unconditional loads (clamped)
+            const int64_t row = ((int64_t)b * p.n_q_heads + hq0 + idx / kHeadDim) * cpu;
+            pre_m[k] = p.part_ml[row * 2 + 0];
+            pre_l[k] = p.part_ml[row * 2 + 1];
+            pre_o[k] = p.part_o[row * kHeadDim + idx % kHeadDim];
+        }
     };
 
     // ---- leave a unit: merge the four wavefronts, write the output or this workgroup's part ----
@@ -433,7 +492,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             const float l_w = wave_sum(l_lane[hh]);
             if (lane == 0) { sm_ml[wave][hh][0] = m_run[hh]; sm_ml[wave][hh][1] = l_w; }
         }
-        __syncthreads();
+        unit_barrier();
 
         // Parts of unit u: one per workgroup whose fp16-row range touches it (these come first), then
         // one per workgroup whose all-quantised range touches it.
@@ -442,10 +501,16 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         const int g = blockIdx.x;
         int ga0, len_a, gb0, len_b;
         contributors(u, ga0, len_a, gb0, len_b);
-        const int n_parts = (sole || hold_put >= 0 || hold_get >= 0) ? 1 : len_a + len_b;
+        // kQuantisedOnly: the only workgroup of a unit's all-quantised range merges the first launch's
+        // parts into its own and writes the output; otherwise the counter runs over the workgroups of
+        // this launch and the last one merges all parts.
+        const bool merge_rows_parts = MODE == kQuantisedOnly && len_a == 1 && len_b > 0;
+        const int n_parts = (sole || hold_put >= 0 || hold_get >= 0 || merge_rows_parts) ? 1 : len_a + len_b;
+        const int n_counted = MODE == kQuantisedOnly ? len_a : n_parts;
         const int part = fp16_phase ? g - gb0 : len_b + g - ga0;
         const int row_stride = cpu;                               // workspace rows per (batch, query head)
-        for (int idx = tid; idx < rep * kHeadDim; idx += 256) {
+        // one output element (query head hh, channel c); p0_*: part 0 of the fp16-row launch (kQuantisedOnly)
+        auto finish_element = [&](int idx, float p0_m, float p0_l, float p0_o) __attribute__((always_inline)) {
             const int hh = idx / kHeadDim, c = idx % kHeadDim;
             float m = -INFINITY;
 #pragma unroll
@@ -475,6 +540,41 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                 const float mn = fmaxf(m, mh);                        // at least one of the two is finite
                 const float f_own = __expf(m - mn), f_held = __expf(mh - mn);
                 p.out[row * kHeadDim + c] = fmaf(o, f_own, oh * f_held) / fmaf(l, f_own, lh * f_held);
+            } else if (merge_rows_parts) {
+                // plain loads: the parts were written by the previous launch
+                // (part 0 was requested when the unit was entered; any further ones eight at a time,
+                // all loads of a batch issued before the first is used)
+                float mm = m, ll = l, oo = o;
+                if (p0_m > -INFINITY) {
+                    const float mn = fmaxf(mm, p0_m);
+                    const float f_old = __expf(mm - mn), f_new = __expf(p0_m - mn);
+                    ll = fmaf(ll, f_old, p0_l * f_new);
+                    oo = fmaf(oo, f_old, p0_o * f_new);
+                    mm = mn;
+                }
+                const float* ml = p.part_ml + (row * row_stride + 1) * 2;
+                const float* po = p.part_o + (row * row_stride + 1) * kHeadDim + c;
+                for (int i0 = 0; i0 < len_b - 1; i0 += 8) {
+                    float mv[8], lv[8], ov[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const int i = min(i0 + j, len_b - 2);
+                        mv[j] = ml[2 * i];
+                        lv[j] = ml[2 * i + 1];
+                        ov[j] = po[(int64_t)i * kHeadDim];
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        if (i0 + j < len_b - 1 && mv[j] > -INFINITY) {
+                            const float mn = fmaxf(mm, mv[j]);
+                            const float f_old = __expf(mm - mn), f_new = __expf(mv[j] - mn);
+                            ll = fmaf(ll, f_old, lv[j] * f_new);
+                            oo = fmaf(oo, f_old, ov[j] * f_new);
+                            mm = mn;
+                        }
+                    }
+                }
+                p.out[row * kHeadDim + c] = oo / ll;
             } else if (n_parts == 1) {
                 p.out[row * kHeadDim + c] = o / l;
             } else {
@@ -485,6 +585,22 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                     device_store(p.part_ml + (row * row_stride + part) * 2 + 1, l);
                 }
             }
+        };
+        if constexpr (MODE == kQuantisedOnly && kPrefetchPart) {
+#pragma unroll
+            for (int k = 0; k < kIdx; ++k)
+                if (tid + 256 * k < rep * kHeadDim) finish_element(tid + 256 * k, pre_m[k], pre_l[k], pre_o[k]);
+        } else {
+            for (int idx = tid; idx < rep * kHeadDim; idx += 256) {
+                float p0_m = -INFINITY, p0_l = 0.f, p0_o = 0.f;
+                if (merge_rows_parts) {
+                    const int64_t row = ((int64_t)b * p.n_q_heads + hq0 + idx / kHeadDim) * cpu;
+                    p0_m = p.part_ml[row * 2 + 0];
+                    p0_l = p.part_ml[row * 2 + 1];
+                    p0_o = p.part_o[row * kHeadDim + idx % kHeadDim];
+                }
+                finish_element(idx, p0_m, p0_l, p0_o);
+            }
         }
         if (n_parts > 1) {
             // the last workgroup to finish this unit merges the parts
@@ -492,7 +608,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             __syncthreads();
             if (tid == 0) {
                 const int done = __hip_atomic_fetch_add(p.counters + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                sm_last = (done == n_parts - 1);
+                sm_last = (done == n_counted - 1);
             }
             __syncthreads();
             if (sm_last) {
@@ -529,23 +645,34 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                 if (tid == 0) __hip_atomic_store(p.counters + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        __syncthreads();          // LDS is reused by the next unit
+        unit_barrier();           // LDS is reused by the next unit
     };
 
     // ---- enter a unit: query operands ----
     auto enter_unit = [&](int u) {
         const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
         const int b = u / p.n_kv_heads;
-        for (int i = tid; i < REP * kHeadDim; i += 256) {
+        auto stage = [&](int i, float x) {
             const int hh = i / kHeadDim, c = i % kHeadDim;
-            const float x = hh < rep ? p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f;
             __half hi, lo;
             split_hi_lo(x, hi, lo);
             sm_q[hh][c] = x;
             sm_qf[2 * hh][c] = hi;
             sm_qf[2 * hh + 1][c] = lo;
+        };
+        if constexpr (MODE == kQuantisedOnly) {
+#pragma unroll
+            for (int k = 0; k < kIdx; ++k) {           // the query was requested one unit ahead
+                const int i = tid + 256 * k;
+                if (i < REP * kHeadDim) stage(i, i / kHeadDim < rep ? p.softmax_scale * __half2float(q_pre[k]) : 0.f);
+            }
+        } else {
+            for (int i = tid; i < REP * kHeadDim; i += 256) {
+                const int hh = i / kHeadDim, c = i % kHeadDim;
+                stage(i, hh < rep ? p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f);
+            }
         }
-        __syncthreads();
+        unit_barrier();
         // per-lane key-side query factors: channels 2*lane, 2*lane+1 times 1/position factor
         const float pf = inv_pos_factor<BITS>(lane & 3);
 #pragma unroll
@@ -628,6 +755,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     };
     const int ub_lo = first_b < last_b ? first_b / max(n_b, 1) : 0;
     const int ub_hi = first_b < last_b ? (last_b - 1) / max(n_b, 1) : -1;
+    if constexpr (MODE != kQuantisedOnly) {
     for (int u = ub_lo; u <= ub_hi; ++u) {
         const int b_lo = max(first_b, u * n_b), b_hi = min(last_b, (u + 1) * n_b);
         if (u > ub_lo) finish_fp16_unit(u - 1);
@@ -822,6 +950,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             if (owns_new) *reinterpret_cast<uint4*>(new_dst) = new_row;
         }
     }
+    }
 
     // ================= phase 2: this workgroup's all-quantised chunks =================
     // Software-pipelined across chunk and unit borders: the next chunk's data is requested while
@@ -839,10 +968,13 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         }
         if (!carry) finish_fp16_unit(ub_hi);
     }
+    if (MODE == kQuantisedOnly && ua_lo <= ua_hi) request_q(ua_lo);
     for (int u = ua_lo; u <= ua_hi; ++u) {
         const int a_lo = max(first_a, u * n_a), a_hi = min(last_a, (u + 1) * n_a);
         const bool carried = carry && u == ua_lo;
+        if (MODE == kQuantisedOnly && kPrefetchPart) request_rows_part(u);
         if (!carried) enter_unit(u);
+        if (MODE == kQuantisedOnly && u < ua_hi) request_q(u + 1);
         for (int ck = a_lo; ck < a_hi; ++ck) {
             const int n_tiles = nx_nt;                   // the chunk requested last is the one processed now
             set_next(ck + 1, false);
@@ -901,14 +1033,14 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 }
 
 // Workgroups the chip holds at once for one instantiation (occupancy query, cached).
-template <int BITS, int REP, int SLOTS, int OCC>
+template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases>
 int resident_workgroups() {
     static int cached = 0;
     if (cached == 0) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC>, 256, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE>, 256, 0) != hipSuccess ||
             cus <= 0 || per_cu <= 0)
             return 256 * OCC;
         cached = cus * per_cu;
@@ -933,7 +1065,27 @@ hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     // every resident workgroup gets an equal share of the cost axis (within one unit of cost)
     const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC>(),
                                                                   p.total_cost / p.cost_b));
-    decode_mfma_kernel<BITS, REP, SLOTS, OCC><<<grid, 256, 0, stream>>>(p);
+    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kBothPhases><<<grid, 256, 0, stream>>>(p);
+    return hipGetLastError();
+}
+
+// The two-launch form: the fp16 rows of all units (residual_rows_kernel), then the all-quantised
+// chunks on a cost axis of their own (unit-major, one unit of cost per chunk).
+template <int BITS, int REP, int SLOTS, int OCC>
+hipError_t launch_two(DecodeParams p, hipStream_t stream) {
+    if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.n_splits_a < 1) return hipErrorInvalidValue;
+    const int64_t units = (int64_t)p.batch * p.n_kv_heads;
+    const int64_t total_a = units * p.plan.n_splits_a;
+    if (total_a > 0x3fffffff) return hipErrorInvalidValue;
+    if (hipError_t e = launch_residual_rows(p, stream); e != hipSuccess) return e;
+    p.k_new = p.v_new = nullptr;                   // the first launch has stored the new token's rows
+    p.total_chunks_a = (int)total_a;
+    p.total_chunks_b = 0;
+    p.cost_b = 1;
+    p.cost_unit = p.plan.n_splits_a;
+    p.total_cost = total_a;
+    const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedOnly>(), total_a);
+    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedOnly><<<grid, 256, 0, stream>>>(p);
     return hipGetLastError();
 }
 
@@ -963,7 +1115,8 @@ hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
     with_variant(p.bits, p.rep_variant, [&](auto v) {
         using V = decltype(v);
-        e = launch_one<V::bits, V::rep, V::slots, V::occ>(p, stream);
+        e = p.two_launches > 0 ? launch_two<V::bits, V::rep, V::slots, V::occ>(p, stream)
+                               : launch_one<V::bits, V::rep, V::slots, V::occ>(p, stream);
     });
     return e;
 }

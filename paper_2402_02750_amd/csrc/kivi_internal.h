@@ -103,6 +103,9 @@ struct DecodeParams {
     // T = units * cost_unit.
     int32_t total_chunks_a, total_chunks_b, cost_b, cost_unit;
     int64_t total_cost;
+    // > 0: the matrix-core family runs as two launches (fp16 rows, then the all-quantised chunks); the
+    // plan then has a single fp16-row split per unit (n_splits_b == 1).
+    int32_t two_launches;
 };
 
 // launchers (each defined next to its kernels); they return hipGetLastError() after the launch
@@ -111,6 +114,9 @@ hipError_t launch_quantize_values(const QuantValueParams& p, hipStream_t stream)
 hipError_t launch_copy_rows(const CopyRowsParams& p, hipStream_t stream);
 hipError_t launch_decode_valu(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream);
+hipError_t launch_residual_rows(const DecodeParams& p, hipStream_t stream);
+// whether launch_residual_rows serves `tiles_b` tiles of fp16 rows on the instantiation for `rep_variant` heads
+bool residual_rows_possible(int tiles_b, int rep_variant);
 hipError_t launch_merge(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t stream);
 

@@ -22,6 +22,8 @@ KIVI_FLUSH_ALG1 = 1
 KIVI_DECODE_AUTO = 0
 KIVI_DECODE_VALU = 1
 KIVI_DECODE_MFMA = 2
+KIVI_DECODE_MFMA_ONE = 3
+KIVI_DECODE_MFMA_TWO = 4
 
 EXPORTS = [
     "kivi_status_string", "kivi_cache_sizes", "kivi_decode_workspace_bytes",

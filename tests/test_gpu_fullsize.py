@@ -24,7 +24,7 @@ def _sample_heads(w, n, seed):
 
 
 @pytest.mark.parametrize("name,n_heads", [("llama7b", 6), ("llama13b_4bit", 4), ("mistral_gqa", 3)])
-@pytest.mark.parametrize("path", [kivi.KIVI_DECODE_AUTO, kivi.KIVI_DECODE_VALU], ids=["auto", "valu"])
+@pytest.mark.parametrize("path", [kivi.KIVI_DECODE_AUTO, kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA_TWO], ids=["auto", "valu", "mfma2"])
 def test_single_step_configs(name, n_heads, path):
     """Benchmark configurations 2, 4 and 5: one decode step at the full shape."""
     torch = gh.require_gpu()

@@ -12,7 +12,7 @@ from paper_2402_02750_amd.workloads import CONFIGS, scaled
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("path", [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA], ids=["valu", "mfma"])
+@pytest.mark.parametrize("path", [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA, kivi.KIVI_DECODE_MFMA_TWO], ids=["valu", "mfma", "mfma2"])
 def test_replayed_launch_matches_eager(path):
     torch = gh.require_gpu()
     # 2 x 2 units of 6000 tokens: several workgroups per unit, so the cross-workgroup merge and

@@ -13,8 +13,8 @@ from paper_2402_02750_amd.workloads import CONFIGS, scaled
 
 pytestmark = pytest.mark.gpu
 
-PATHS = [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA]
-PATH_IDS = ["valu", "mfma"]
+PATHS = [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA, kivi.KIVI_DECODE_MFMA_TWO]
+PATH_IDS = ["valu", "mfma", "mfma2"]
 
 
 def _run_case(w, length, policy, path, heads=None):
