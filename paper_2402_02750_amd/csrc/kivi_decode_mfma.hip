@@ -955,6 +955,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // ================= phase 2: this workgroup's all-quantised chunks =================
     // Software-pipelined across chunk and unit borders: the next chunk's data is requested while
     // the current one is consumed.
+    if constexpr (MODE == kQuantisedOnly) {         // the first query ahead of the first chunk: loads return in order
+        if (first_a < last_a) request_q(first_a / n_a);
+    }
     initial_request();                              // overlaps the merge of the last fp16-row unit
     // If the last unit of phase 1 is the first unit of phase 2 and no other workgroup touches it, its
     // running state simply carries over: no part, no merge.
@@ -968,7 +971,6 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         }
         if (!carry) finish_fp16_unit(ub_hi);
     }
-    if (MODE == kQuantisedOnly && ua_lo <= ua_hi) request_q(ua_lo);
     for (int u = ua_lo; u <= ua_hi; ++u) {
         const int a_lo = max(first_a, u * n_a), a_hi = min(last_a, (u + 1) * n_a);
         const bool carried = carry && u == ua_lo;
