@@ -217,7 +217,11 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
         const int64_t units = (int64_t)l->batch * l->n_kv_heads;
         const int resident = mfma_geometry(l->bits, std::min(l->n_q_heads / l->n_kv_heads, kMaxRep)).resident_workgroups;
         // (measured at 32 heads, context 4096, 2 bits: equal at 1 unit per workgroup, 4-6 % faster from 1.5 on)
-        two = possible && (l->decode_path == KIVI_DECODE_MFMA_TWO || units * 4 >= (int64_t)resident * 5);
+        // The 4-bit instantiation for 5 to 8 query heads per kv-head spills registers in its single-launch
+        // form and not in the other: two launches there at every size measured (16 to 128 units:
+        // 89 -> 75, 83 -> 69, 123 -> 87 us).
+        const bool spilling = rep_variant == 8 && l->bits == 4;
+        two = possible && (l->decode_path == KIVI_DECODE_MFMA_TWO || spilling || units * 4 >= (int64_t)resident * 5);
     }
     p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
     p.two_launches = two ? 1 : 0;
