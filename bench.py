@@ -141,6 +141,7 @@ def run_stream(args, w, path_name, path):
                                f"prompt {w.prompt} + {w.decode_steps} decode steps, {w.bits}-bit, G=32, R={w.residual}, "
                                f"{flushes} flushes of one group",
                    "decode_path": path_name,
+                   "attention_launches": kivi.kivi_decode_plan(layout, cache).launches,
                    "step": "kivi_decode_step: append newest token + flush (every 32nd step) + decode attention"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
@@ -278,6 +279,7 @@ def main():
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads, "
                                f"head_dim 128, context {L} = {n_q} quantised ({w.bits}-bit, G=32) + {n_r} fp16 residual",
                    "decode_path": args.path, "cache_copies_rotated": len(caches),
+                   "attention_launches": kivi.kivi_decode_plan(layout, caches[0]).launches,
                    "step": "kivi_decode_step: append newest token + flush check + decode attention"},
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -127,6 +127,19 @@ const char* kivi_status_string(int status);
 /* Host helper: buffer sizes for `layout`.  Errors: INVALID_ARG, UNSUPPORTED. */
 int kivi_cache_sizes(const kivi_layout_t* layout, kivi_cache_sizes_t* sizes);
 
+/* How kivi_decode_attention would serve a cache state: which kernel family, how many launches per
+ * group of up to 8 query heads per kv-head, and how the token axis is cut. */
+typedef struct kivi_decode_plan {
+    int32_t family;             /* KIVI_DECODE_VALU or KIVI_DECODE_MFMA                              */
+    int32_t launches;           /* kernel launches of one attention call                            */
+    int32_t splits_quantised;   /* pieces of the all-quantised token range per (batch, kv-head)     */
+    int32_t splits_fp16;        /* pieces of the range that holds fp16 rows                         */
+    int32_t tiles_per_split_quantised, tiles_per_split_fp16;   /* in 32-token tiles                */
+} kivi_decode_plan_t;
+
+/* Host helper: the plan for `cache`'s current state (no launch).  Errors: INVALID_ARG, UNSUPPORTED. */
+int kivi_decode_plan(const kivi_layout_t* layout, const kivi_cache_t* cache, kivi_decode_plan_t* plan);
+
 /* Host helper: bytes of workspace kivi_decode_attention needs for ANY cache state that fits
  * `layout` (partial softmax statistics and outputs of the context splits). */
 int kivi_decode_workspace_bytes(const kivi_layout_t* layout, size_t* bytes);

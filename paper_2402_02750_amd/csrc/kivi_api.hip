@@ -178,6 +178,27 @@ int decode_family(const kivi_layout_t* l) {
     return mfma_geometry(l->bits, rep).chunk_tiles == 0 ? KIVI_DECODE_VALU : KIVI_DECODE_MFMA;
 }
 
+// The matrix-core family as two launches (fp16 rows first, then the all-quantised chunks): possible
+// when the cache has both parts and K and V are split at the same token; chosen when asked for,
+// or when a workgroup of the persistent kernel would own several (batch, kv-head) units -- their
+// fp16-row chunks would then run one after the other, each a chain of dependent steps.
+bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path) {
+    if (path != KIVI_DECODE_MFMA || l->decode_path == KIVI_DECODE_MFMA_ONE) return false;
+    const int rep_launch = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
+    const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
+    const int tiles_b = ceil_div(c->n_kq + c->n_kr, kTileTokens) - c->n_kq / kTileTokens;
+    const bool possible = c->n_kq == c->n_vq && c->n_kq >= kTileTokens && c->n_kr > 0 &&
+                          residual_rows_possible(tiles_b, rep_variant);
+    const int64_t units = (int64_t)l->batch * l->n_kv_heads;
+    const int resident = mfma_geometry(l->bits, rep_launch).resident_workgroups;
+    // (measured at 32 heads, context 4096, 2 bits: equal at 1 unit per workgroup, 4-6 % faster from 1.5 on)
+    // The 4-bit instantiation for 5 to 8 query heads per kv-head spills registers in its single-launch
+    // form and not in the other: two launches there at every size measured (16 to 128 units:
+    // 89 -> 75, 83 -> 69, 123 -> 87 us).
+    const bool spilling = rep_variant == 8 && l->bits == 4;
+    return possible && (l->decode_path == KIVI_DECODE_MFMA_TWO || spilling || units * 4 >= (int64_t)resident * 5);
+}
+
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the
 // rows of token length-1 are not in the rings yet and the (matrix-core) kernel puts them there.
 int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, float softmax_scale,
@@ -203,26 +224,7 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     const int path = decode_family(l);
     if ((k_new || v_new) && path != KIVI_DECODE_MFMA) return KIVI_ERR_UNSUPPORTED;
     p.k_new = static_cast<const __half*>(k_new); p.v_new = static_cast<const __half*>(v_new);
-    // The matrix-core family as two launches (fp16 rows first, then the all-quantised chunks): possible
-    // when the cache has both parts and K and V are split at the same token; chosen when asked for,
-    // or when a workgroup of the persistent kernel would own several (batch, kv-head) units -- their
-    // fp16-row chunks would then run one after the other, each a chain of dependent steps.
-    bool two = false;
-    if (path == KIVI_DECODE_MFMA && l->decode_path != KIVI_DECODE_MFMA_ONE) {
-        const int rep_launch = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
-        const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
-        const int tiles_b = ceil_div(c->n_kq + c->n_kr, kTileTokens) - c->n_kq / kTileTokens;
-        const bool possible = c->n_kq == c->n_vq && c->n_kq >= kTileTokens && c->n_kr > 0 &&
-                              residual_rows_possible(tiles_b, rep_variant);
-        const int64_t units = (int64_t)l->batch * l->n_kv_heads;
-        const int resident = mfma_geometry(l->bits, std::min(l->n_q_heads / l->n_kv_heads, kMaxRep)).resident_workgroups;
-        // (measured at 32 heads, context 4096, 2 bits: equal at 1 unit per workgroup, 4-6 % faster from 1.5 on)
-        // The 4-bit instantiation for 5 to 8 query heads per kv-head spills registers in its single-launch
-        // form and not in the other: two launches there at every size measured (16 to 128 units:
-        // 89 -> 75, 83 -> 69, 123 -> 87 us).
-        const bool spilling = rep_variant == 8 && l->bits == 4;
-        two = possible && (l->decode_path == KIVI_DECODE_MFMA_TWO || spilling || units * 4 >= (int64_t)resident * 5);
-    }
+    const bool two = wants_two_launches(l, c, path);
     p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
     p.two_launches = two ? 1 : 0;
     const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
@@ -305,6 +307,22 @@ int kivi_cache_sizes(const kivi_layout_t* l, kivi_cache_sizes_t* out) {
     out->k_scale = out->k_zero = units * tiles * kHeadDim * 2;
     out->v_scale = out->v_zero = units * (size_t)l->cap_q_tokens * (kHeadDim / kTileTokens) * 2;
     out->k_resid = out->v_resid = units * (size_t)l->cap_r_tokens * kHeadDim * 2;
+    return KIVI_OK;
+}
+
+int kivi_decode_plan(const kivi_layout_t* l, const kivi_cache_t* c, kivi_decode_plan_t* out) {
+    if (int st = check_layout(l)) return st;
+    if (int st = check_cache(l, c)) return st;
+    if (!out) return KIVI_ERR_INVALID_ARG;
+    const int path = decode_family(l);
+    const bool two = wants_two_launches(l, c, path);
+    const SplitPlan plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
+    out->family = path;
+    out->launches = path == KIVI_DECODE_MFMA ? (two ? 2 : 1) : 2;       // vector-ALU family: decode + merge
+    out->splits_quantised = plan.n_splits_a;
+    out->splits_fp16 = plan.n_splits_b;
+    out->tiles_per_split_quantised = plan.tiles_per_split_a;
+    out->tiles_per_split_fp16 = plan.tiles_per_split_b;
     return KIVI_OK;
 }
 

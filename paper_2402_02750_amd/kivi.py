@@ -26,7 +26,7 @@ KIVI_DECODE_MFMA_ONE = 3
 KIVI_DECODE_MFMA_TWO = 4
 
 EXPORTS = [
-    "kivi_status_string", "kivi_cache_sizes", "kivi_decode_workspace_bytes",
+    "kivi_status_string", "kivi_cache_sizes", "kivi_decode_workspace_bytes", "kivi_decode_plan",
     "kivi_quantize_key_groups", "kivi_quantize_value_tokens", "kivi_prefill", "kivi_append_residual",
     "kivi_flush_residual", "kivi_decode_attention", "kivi_decode_step", "kivi_stream_read_probe",
     "kivi_batch_slice", "kivi_decode_step_ragged", "kivi_decode_attention_ragged",
@@ -55,6 +55,11 @@ class kivi_seq_state_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("n_kq", "n_vq", "k_r_start", "n_kr", "v_r_start", "n_vr")]
 
 
+class kivi_decode_plan_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("family", "launches", "splits_quantised", "splits_fp16",
+                                              "tiles_per_split_quantised", "tiles_per_split_fp16")]
+
+
 class kivi_cache_sizes_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in (
         "k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_resid", "v_resid")]
@@ -78,6 +83,7 @@ def load_library() -> ctypes.CDLL:
     lib.kivi_status_string.argtypes = [ctypes.c_int]
     lib.kivi_cache_sizes.argtypes = [P(kivi_layout_t), P(kivi_cache_sizes_t)]
     lib.kivi_decode_workspace_bytes.argtypes = [P(kivi_layout_t), P(ctypes.c_size_t)]
+    lib.kivi_decode_plan.argtypes = [P(kivi_layout_t), P(kivi_cache_t), P(kivi_decode_plan_t)]
     for name in ("kivi_quantize_key_groups", "kivi_quantize_value_tokens"):
         getattr(lib, name).argtypes = [P(kivi_layout_t), VP, I64, I64, I64, I32, P(kivi_cache_t), VP]
     lib.kivi_prefill.argtypes = [P(kivi_layout_t), VP, I64, I64, I64, VP, I64, I64, I64, I32, I32,
@@ -120,6 +126,14 @@ def kivi_cache_sizes(layout: kivi_layout_t) -> kivi_cache_sizes_t:
     sizes = kivi_cache_sizes_t()
     _check(load_library().kivi_cache_sizes(ctypes.byref(layout), ctypes.byref(sizes)), "kivi_cache_sizes")
     return sizes
+
+
+def kivi_decode_plan(layout: kivi_layout_t, cache) -> kivi_decode_plan_t:
+    """How kivi_decode_attention would serve the cache's current state (`cache`: a Cache or kivi_cache_t)."""
+    plan = kivi_decode_plan_t()
+    c = cache.c if hasattr(cache, "c") else cache
+    _check(load_library().kivi_decode_plan(ctypes.byref(layout), ctypes.byref(c), ctypes.byref(plan)), "kivi_decode_plan")
+    return plan
 
 
 def kivi_decode_workspace_bytes(layout: kivi_layout_t) -> int:

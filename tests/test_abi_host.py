@@ -211,3 +211,35 @@ def test_batch_slice_and_ragged_validate(lib):
     before = bytes(states)
     assert step(ctypes.byref(l), ctypes.byref(c), states, good, good, good, 0.1, 0, out, good, 1 << 30, None) == kivi.KIVI_ERR_INVALID_ARG
     assert bytes(states) == before
+
+
+def test_decode_plan(lib):
+    """kivi_decode_plan: family, launches and splits for a cache state, without any launch."""
+    def plan(batch, hq, hkv, bits, n_q, n_r, path=kivi.KIVI_DECODE_AUTO, n_vq=None, n_vr=None):
+        l = kivi.make_layout(batch, hq, hkv, bits, 128, max(n_q, 32) + 64, 192, decode_path=path)
+        c = _fake_cache(n_kq=n_q, n_kr=n_r, n_vq=n_q if n_vq is None else n_vq, n_vr=n_r if n_vr is None else n_vr)
+        return kivi.kivi_decode_plan(l, c)
+
+    # one (batch, kv-head) unit per resident workgroup: the single launch, 16-tile chunks, one fp16-row chunk
+    p = plan(16, 32, 32, 2, 3968, 128)
+    assert (p.family, p.launches) == (kivi.KIVI_DECODE_MFMA, 1)
+    assert (p.splits_quantised, p.tiles_per_split_quantised, p.splits_fp16, p.tiles_per_split_fp16) == (8, 16, 1, 4)
+    # four units per workgroup: fp16 rows in a launch of their own, one part per unit
+    p = plan(64, 32, 32, 2, 1920, 150)
+    assert (p.family, p.launches, p.splits_fp16, p.tiles_per_split_fp16) == (kivi.KIVI_DECODE_MFMA, 2, 1, 5)
+    assert plan(64, 32, 32, 2, 1920, 150, path=kivi.KIVI_DECODE_MFMA_ONE).launches == 1
+    assert plan(16, 32, 32, 2, 3968, 128, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 2
+    # two launches need both parts and K and V split at the same token
+    assert plan(64, 32, 32, 2, 0, 100, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 1
+    assert plan(64, 32, 32, 2, 1920, 0, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 1
+    assert plan(64, 32, 32, 2, 1920, 150, n_vq=1984, n_vr=86).launches == 1
+    # 4-bit, 8 query heads per kv-head: two launches at any size
+    assert plan(2, 64, 8, 4, 4096, 128).launches == 2
+    assert plan(2, 64, 8, 2, 4096, 128).launches == 1
+    # vector-ALU family: decode + merge
+    p = plan(16, 32, 32, 2, 3968, 128, path=kivi.KIVI_DECODE_VALU)
+    assert (p.family, p.launches) == (kivi.KIVI_DECODE_VALU, 2)
+    bad = kivi.kivi_decode_plan_t()
+    l = _layout()
+    assert lib.kivi_decode_plan(ctypes.byref(l), None, ctypes.byref(bad)) == kivi.KIVI_ERR_INVALID_ARG
+    assert lib.kivi_decode_plan(ctypes.byref(l), ctypes.byref(_fake_cache()), None) == kivi.KIVI_ERR_INVALID_ARG
