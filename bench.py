@@ -32,6 +32,9 @@ MEASURED_TRAFFIC = {
     # profiles/decode_mfma_llama7b.md: FETCH_SIZE 111996.2 KiB x 2.0 + WRITE_SIZE 387.1 KiB x 1.0
     ("llama7b", "mfma"): 111996.2 * 1024 * 2.0 + 387.1 * 1024,
     ("llama7b", "auto"): 111996.2 * 1024 * 2.0 + 387.1 * 1024,
+    # profiles/decode_mfma_other_workloads.md, stream: mean per step of the two attention kernels
+    # (73891.9 + 196238.2) KiB x 2.0 read, (2080.0 + 1024.0) KiB written
+    ("stream", "auto"): (73891.9 + 196238.2) * 1024 * 2.0 + (2080.0 + 1024.0) * 1024,
 }
 
 
@@ -144,7 +147,7 @@ def run_stream(args, w, path_name, path):
                    "attention_launches": kivi.kivi_decode_plan(layout, cache).launches,
                    "step": "kivi_decode_step: append newest token + flush (every 32nd step) + decode attention"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((w.name, path_name)),
                      "kernel": "whole steps (attention kernel plus, on flush steps, the copy and quantise kernels): "
                                "sum of the attention's algorithmic bytes over the steps / time of all steps",
                      "algorithmic_bytes_per_launch": bytes_total / w.decode_steps},
