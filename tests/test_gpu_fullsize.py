@@ -123,7 +123,7 @@ def test_arrays_beyond_4GiB():
     oc.prefill(k_s, v_s)
     q = workloads.queries(w)
     ref = gh.oracle_attention_for_heads(w, oc, q, heads)
-    for path in (kivi.KIVI_DECODE_AUTO, kivi.KIVI_DECODE_VALU):
+    for path in (kivi.KIVI_DECODE_AUTO, kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA_TWO):
         print(f"case beyond4g: path {path}", flush=True)
         layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, gh.round_up(T, 32), 192,
                                   decode_path=path)
