@@ -9,6 +9,8 @@
 
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 namespace kivi {
 namespace {
 
@@ -45,14 +47,16 @@ __device__ __forceinline__ uint32_t encode(float x, float z, float s, float leve
 struct GroupConst { float z, s, y, c0, tol; };
 
 __device__ __forceinline__ GroupConst group_const(float lo, float s) {
-    const float y = s == 0.0f ? 0.0f : 1.0f / s;
+    // y: the hardware reciprocal (1 ulp: relative error <= 2^-23), one instruction instead of a division
+    const float y = s == 0.0f ? 0.0f : __builtin_amdgcn_rcpf(s);
     const float c0 = -lo * y;
     // q' = fl(x * y + c0) against the contract's q = fl(fl(x - z) / s), with Q the exact quotient:
-    // |q - Q| <= Q * 2^-23 and |q' - Q| <= Q * 2^-23 + |z / s| * 2^-24 * 1.001 (roundings of y, c0 and
-    // of the sum), so for Q <= 16.1:  |q' - q| < 3.9e-6 + |c0| * 6.1e-8.  Twice that as tolerance.
+    // |q - Q| <= Q * 2^-23 and |q' - Q| <= Q * 2^-22 + |z / s| * 2^-22 * 1.001 (error of y in both
+    // products, roundings of c0 and of the sum), so for Q <= 16.1:  |q' - q| < 5.8e-6 + |c0| * 2.4e-7.
+    // Twice that as tolerance.
     // (scale below the smallest normal fp16 number: its rounding error is not relative, the quotient
     // can pass `levels`: tolerance 1 = always the exact path)
-    return GroupConst{lo, s, y, c0, (s != 0.0f && s < 6.103515625e-05f) ? 1.0f : 8e-6f + fabsf(c0) * 1.3e-7f};
+    return GroupConst{lo, s, y, c0, (s != 0.0f && s < 6.103515625e-05f) ? 1.0f : 1.2e-5f + fabsf(c0) * 4.8e-7f};
 }
 
 // The same code as encode() without a division per element: one fused multiply-add straight from
@@ -69,11 +73,18 @@ __device__ __forceinline__ float encode_fast(__half x, const GroupConst& g, floa
     return r;
 }
 
-// maximum over the 64 lanes of a wavefront (every lane gets it)
+// maximum over the 64 lanes of a wavefront (every lane gets it): DPP moves inside the rows of 16
+// lanes, then the four rows through scalar registers
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m));
-    return v;
+    auto dpp = [](float x, auto ctrl) {
+        return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    v = fmaxf(v, dpp(v, std::integral_constant<int, 0xB1>{}));     // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp(v, std::integral_constant<int, 0x4E>{}));     // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp(v, std::integral_constant<int, 0x141>{}));    // lane i <-> 7 - i within 8
+    v = fmaxf(v, dpp(v, std::integral_constant<int, 0x140>{}));    // lane i <-> 15 - i within 16
+    auto lane = [&](int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); };
+    return fmaxf(fmaxf(lane(0), lane(16)), fmaxf(lane(32), lane(48)));
 }
 
 // A 32-bit word assembled from float codes: the low and the high 16 bits each stay exact in fp32.
