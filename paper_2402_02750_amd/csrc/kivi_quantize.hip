@@ -15,9 +15,19 @@ namespace kivi {
 namespace {
 
 typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-// packed fp16 minimum / maximum (v_pk_min_f16 / v_pk_max_f16): exact, no arithmetic
-__device__ __forceinline__ half2v pk_min(half2v a, half2v b) { return __builtin_elementwise_min(a, b); }
-__device__ __forceinline__ half2v pk_max(half2v a, half2v b) { return __builtin_elementwise_max(a, b); }
+// packed fp16 minimum / maximum (v_pk_min_f16 / v_pk_max_f16): exact, no arithmetic.  Written as
+// instructions: the builtins make the compiler quiet signalling NaNs first (one more instruction per
+// operand), which finite inputs -- the precondition of the quantiser -- do not need.
+__device__ __forceinline__ half2v pk_min(half2v a, half2v b) {
+    half2v r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ half2v pk_max(half2v a, half2v b) {
+    half2v r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
 
 // consecutive value tiles one workgroup walks, the next tile's rows prefetched (measured at the
 // 3968-token prefill of 512 units: 209 us with 1, 190 us with 4; the key kernel got slower with it)
@@ -129,11 +139,21 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
     constexpr float levels = (float)((1 << BITS) - 1);
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
 
+    if (p.src.ring_cap > 0) {
 #pragma unroll
-    for (int pass = 0; pass < 2 * TG; ++pass) {
-        const int row = pass * 16 + (tid >> 4), seg = tid & 15;
-        *reinterpret_cast<uint4*>(&tile[row][seg * 8]) = *reinterpret_cast<const uint4*>(
-            p.src.base + row_offset(p.src, b, h, g * kRows + row) + seg * 8);
+        for (int pass = 0; pass < 2 * TG; ++pass) {
+            const int row = pass * 16 + (tid >> 4), seg = tid & 15;
+            *reinterpret_cast<uint4*>(&tile[row][seg * 8]) = *reinterpret_cast<const uint4*>(
+                p.src.base + row_offset(p.src, b, h, g * kRows + row) + seg * 8);
+        }
+    } else {
+        // a plain source (prefill): one row address per thread, the other passes lie 16 rows further each
+        const __half* src = p.src.base + row_offset(p.src, b, h, g * kRows + (tid >> 4)) + (tid & 15) * 8;
+        const int64_t step = 16 * p.src.stride_t;
+#pragma unroll
+        for (int pass = 0; pass < 2 * TG; ++pass)
+            *reinterpret_cast<uint4*>(&tile[pass * 16 + (tid >> 4)][(tid & 15) * 8]) =
+                *reinterpret_cast<const uint4*>(src + pass * step);
     }
     __syncthreads();
 
