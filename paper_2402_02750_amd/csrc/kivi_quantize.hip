@@ -51,9 +51,11 @@ __device__ __forceinline__ uint32_t encode(float x, float z, float s, float leve
     return s == 0.0f ? 0u : (uint32_t)r;
 }
 
-// Group constants kept in LDS: zero-point and scale (for the exact path), and for the fast path
-// y = fl(1/s), c0 = fl(-z * y) and the tolerance below (y = c0 = 0 when the scale is 0, which
-// makes every code of the group 0).
+// Group constants: zero-point and scale (for the exact path), and for the fast path y ~ 1/s,
+// c0 = fl(-z * y) and the tolerance below (y = c0 = 0 when the scale is 0, which makes every code
+// of the group 0).  The key kernel keeps them in LDS as one array per constant, so that the
+// constants of the consecutive channels a word covers are read as vectors (3 % on that kernel; the
+// same for the consecutive tokens of a value word gained 3 % at 4 bits and lost 4 % at 2 bits).
 struct GroupConst { float z, s, y, c0, tol; };
 
 __device__ __forceinline__ GroupConst group_const(float lo, float s) {
@@ -76,8 +78,8 @@ __device__ __forceinline__ GroupConst group_const(float lo, float s) {
 // above -tolerance, and with a normal fp16 scale s >= (max - min) / levels * (1 - 2^-11) it stays
 // below levels + 0.008; a group whose scale is an fp16 subnormal gets a tolerance that sends its
 // tile down the exact path (group_const).  Returns the code as a float.
-__device__ __forceinline__ float encode_fast(__half x, const GroupConst& g, float& dev) {
-    const float q = fmaf(__half2float(x), g.y, g.c0);
+__device__ __forceinline__ float encode_fast(__half x, float y, float c0, float& dev) {
+    const float q = fmaf(__half2float(x), y, c0);
     const float r = __builtin_rintf(q);
     dev = fmaxf(dev, fabsf(q - r));
     return r;
@@ -132,7 +134,7 @@ template <int BITS, int TG>
 __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
     constexpr int kRows = TG * kTileTokens;
     __shared__ __align__(16) __half tile[kRows][kRowPad];
-    __shared__ GroupConst sh_g[kHeadDim];
+    __shared__ __align__(16) float sh_y[kHeadDim], sh_c0[kHeadDim], sh_z[kHeadDim], sh_s[kHeadDim];
     __shared__ float sh_tol[4];         // per wavefront: largest fast-path tolerance of its groups
     __shared__ half2v sh_lo[4][kHeadDim / 2], sh_hi[4][kHeadDim / 2];
     const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
             p.zero[o] = __float2half_rn(lo);
         }
         const GroupConst gc = group_const(lo, __half2float(s16));
-        sh_g[tid] = gc;
+        sh_y[tid] = gc.y; sh_c0[tid] = gc.c0; sh_z[tid] = gc.z; sh_s[tid] = gc.s;
         const float wt = wave_max(gc.tol);                    // tid < 128: wavefronts 0 and 1, all lanes active
         if ((tid & 63) == 0) sh_tol[tid >> 6] = wt;
     }
@@ -224,13 +226,18 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
         }
         WordAcc acc;
         float dev = 0.0f;
+        float ys[RUN], cs[RUN];
+#pragma unroll
+        for (int el = 0; el < RUN; el += 4) {
+            *reinterpret_cast<float4*>(&ys[el]) = *reinterpret_cast<const float4*>(&sh_y[c0 + el]);
+            *reinterpret_cast<float4*>(&cs[el]) = *reinterpret_cast<const float4*>(&sh_c0[c0 + el]);
+        }
 #pragma unroll
         for (int el = 0; el < RUN; ++el) {
-            const GroupConst gc = sh_g[c0 + el];
 #pragma unroll
             for (int uo = 0; uo < 2; ++uo) {
                 const int bit = (el & 1) * 16 + (BITS == 2 ? 2 * (uo * 4 + (el >> 1)) : 4 * (uo * 2 + ((el >> 1) & 1)));
-                acc.add(encode_fast(x[uo].h[el], gc, dev), bit);
+                acc.add(encode_fast(x[uo].h[el], ys[el], cs[el], dev), bit);
             }
         }
         uint32_t w = acc.word();
@@ -238,11 +245,10 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
             w = 0;
 #pragma unroll
             for (int el = 0; el < RUN; ++el) {
-                const GroupConst gc = sh_g[c0 + el];
 #pragma unroll
                 for (int uo = 0; uo < 2; ++uo) {
                     const int bit = (el & 1) * 16 + (BITS == 2 ? 2 * (uo * 4 + (el >> 1)) : 4 * (uo * 2 + ((el >> 1) & 1)));
-                    w |= encode(__half2float(x[uo].h[el]), gc.z, gc.s, levels) << bit;
+                    w |= encode(__half2float(x[uo].h[el]), sh_z[c0 + el], sh_s[c0 + el], levels) << bit;
                 }
             }
         }
@@ -337,7 +343,7 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
             const int c = u * 16 + (lane & 15);
             const int t = (lane >> 4) * 8 + e;
             if (full || (t >= lo_tok && t < hi_tok)) {
-                acc.add(encode_fast(tile[t][c], sh_g[t][c >> 5], dev), bit);
+                acc.add(encode_fast(tile[t][c], sh_g[t][c >> 5].y, sh_g[t][c >> 5].c0, dev), bit);
                 mask |= (uint32_t)((1 << BITS) - 1) << bit;
             }
         }
