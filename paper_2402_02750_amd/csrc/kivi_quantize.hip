@@ -332,7 +332,11 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
 
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
     uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;
-    for (int wd = tid; wd < kWords; wd += 256) {
+    // One word of the packed tile.  FULL: every token of the tile is written by this call (the case
+    // of a prefill) -- no test per code; otherwise only the tokens [lo_tok, hi_tok) are encoded and
+    // the other codes of the word, written by earlier calls, are kept.
+    auto encode_word = [&](int wd, auto full_tag) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full_tag)::value;
         WordAcc acc;
         uint32_t mask = 0;
         float dev = 0.0f;
@@ -342,7 +346,7 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
             word_coords<BITS>(wd, bit, lane, u, e);
             const int c = u * 16 + (lane & 15);
             const int t = (lane >> 4) * 8 + e;
-            if (full || (t >= lo_tok && t < hi_tok)) {
+            if (FULL || (t >= lo_tok && t < hi_tok)) {
                 acc.add(encode_fast(tile[t][c], sh_g[t][c >> 5].y, sh_g[t][c >> 5].c0, dev), bit);
                 mask |= (uint32_t)((1 << BITS) - 1) << bit;
             }
@@ -356,16 +360,21 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
                 word_coords<BITS>(wd, bit, lane, u, e);
                 const int c = u * 16 + (lane & 15);
                 const int t = (lane >> 4) * 8 + e;
-                if (t >= lo_tok && t < hi_tok)
+                if (FULL || (t >= lo_tok && t < hi_tok))
                     w |= encode(__half2float(tile[t][c]), sh_g[t][c >> 5].z, sh_g[t][c >> 5].s, levels) << bit;
             }
         }
-        if (full) {
+        if (FULL) {
             dst[wd] = w;
         } else if (mask) {
             // a partly filled tile: keep the codes of the tokens written by earlier calls
             dst[wd] = (dst[wd] & ~mask) | w;
         }
+    };
+    if (full) {
+        for (int wd = tid; wd < kWords; wd += 256) encode_word(wd, std::true_type{});
+    } else {
+        for (int wd = tid; wd < kWords; wd += 256) encode_word(wd, std::false_type{});
     }
     __syncthreads();          // the tile and the group constants are overwritten by the next tile
     }
