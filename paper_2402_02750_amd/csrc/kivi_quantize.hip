@@ -260,6 +260,7 @@ template <int BITS>
 __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p) {
     __shared__ __align__(16) __half tile[kTileTokens][kRowPad];
     __shared__ GroupConst sh_g[kTileTokens][4];
+    __shared__ float2 sh_mm[kTileTokens][4];    // per (token, 32-channel block): group minimum, maximum
     __shared__ float sh_tol[4];         // per wavefront: largest fast-path tolerance of its groups
     const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     constexpr float levels = (float)((1 << BITS) - 1);
@@ -314,13 +315,21 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         // which is what the decode kernels read)
         if (p.group_blocks >= 2) { lo = fminf(lo, __shfl_xor(lo, 2)); hi = fmaxf(hi, __shfl_xor(hi, 2)); }
         if (p.group_blocks >= 4) { lo = fminf(lo, __shfl_xor(lo, 4)); hi = fmaxf(hi, __shfl_xor(hi, 4)); }
+        if (part == 0) sh_mm[t][cg] = make_float2(lo, hi);
+    }
+    __syncthreads();
+    // the group constants on two wavefronts with every lane busy (one (token, channel block) each)
+    // instead of on every other lane of all four
+    if (tid < 4 * kTileTokens) {
+        const int t = tid >> 2, cg = tid & 3;
         float my_tol = 0.0f;
-        if (part == 0 && t >= lo_tok && t < hi_tok) {
-            const __half s16 = __float2half_rn((hi - lo) / levels);
+        if (t >= lo_tok && t < hi_tok) {
+            const float2 mm = sh_mm[t][cg];
+            const __half s16 = __float2half_rn((mm.y - mm.x) / levels);
             const int64_t o = ((unit * p.cap_tiles + dst_tile) * kTileTokens + t) * 4 + cg;
             p.scale[o] = s16;
-            p.zero[o] = __float2half_rn(lo);
-            const GroupConst gc = group_const(lo, __half2float(s16));
+            p.zero[o] = __float2half_rn(mm.x);
+            const GroupConst gc = group_const(mm.x, __half2float(s16));
             sh_g[t][cg] = gc;
             my_tol = gc.tol;
         }
@@ -328,7 +337,7 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         if ((tid & 63) == 0) sh_tol[tid >> 6] = wt;
     }
     __syncthreads();
-    const float tile_tol = fmaxf(fmaxf(sh_tol[0], sh_tol[1]), fmaxf(sh_tol[2], sh_tol[3]));
+    const float tile_tol = fmaxf(sh_tol[0], sh_tol[1]);
 
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
     uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;
