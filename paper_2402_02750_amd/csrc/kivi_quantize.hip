@@ -308,13 +308,21 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         const half2v hi2 = pk_max(pk_max(pk_max(a.h[0], a.h[1]), pk_max(a.h[2], a.h[3])),
                               pk_max(pk_max(c.h[0], c.h[1]), pk_max(c.h[2], c.h[3])));
         float lo = fminf((float)lo2.x, (float)lo2.y), hi = fmaxf((float)hi2.x, (float)hi2.y);
-        lo = fminf(lo, __shfl_xor(lo, 1));
-        hi = fmaxf(hi, __shfl_xor(hi, 1));
+        // partner lanes by DPP moves: xor 1 and xor 2 as quad permutations; for xor 4 the mirror
+        // inside 8 lanes does, because by then the four lanes of a quad hold the same value
+        auto dpp = [](float x, auto ctrl) {
+            return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, true));
+        };
+        const std::integral_constant<int, 0xB1> xor1{};
+        const std::integral_constant<int, 0x4E> xor2{};
+        const std::integral_constant<int, 0x141> mirror8{};
+        lo = fminf(lo, dpp(lo, xor1));
+        hi = fmaxf(hi, dpp(hi, xor1));
         // G = 64 or 128 channels per group: combine 2 or 4 neighbouring 32-channel blocks; every
         // block then stores the group's scale and zero-point (replicated at 32-channel granularity,
         // which is what the decode kernels read)
-        if (p.group_blocks >= 2) { lo = fminf(lo, __shfl_xor(lo, 2)); hi = fmaxf(hi, __shfl_xor(hi, 2)); }
-        if (p.group_blocks >= 4) { lo = fminf(lo, __shfl_xor(lo, 4)); hi = fmaxf(hi, __shfl_xor(hi, 4)); }
+        if (p.group_blocks >= 2) { lo = fminf(lo, dpp(lo, xor2)); hi = fmaxf(hi, dpp(hi, xor2)); }
+        if (p.group_blocks >= 4) { lo = fminf(lo, dpp(lo, mirror8)); hi = fmaxf(hi, dpp(hi, mirror8)); }
         if (part == 0) sh_mm[t][cg] = make_float2(lo, hi);
     }
     __syncthreads();
