@@ -222,9 +222,10 @@ int kivi_decode_attention(const kivi_layout_t* layout, const kivi_cache_t* cache
  * One whole decoding step of Algorithm 1 (Decoding) -- append (t_K, t_V) to the fp16 residual
  * parts, flush them per `policy`, attention of t_Q over the updated cache -- in as few launches
  * as possible.  The result is the same as kivi_append_residual + kivi_flush_residual +
- * kivi_decode_attention.  On steps where nothing is flushed and the matrix-core family runs, it
- * is ONE launch: the attention kernel reads the new token's rows from k_new / v_new and writes
- * them into the residual rings itself.  On the other steps it enqueues the separate kernels.
+ * kivi_decode_attention.  On steps where nothing is flushed and the matrix-core family runs, the
+ * append costs no launch of its own: the attention (one launch, or two on large batches, see
+ * kivi_decode_plan) reads the new token's rows from k_new / v_new and writes them into the
+ * residual rings itself.  On the other steps it enqueues the separate kernels.
  *   k_new, v_new   device, fp16 [b][n_kv_heads][128]; they must stay valid until the launch has run
  *   other arguments as for kivi_decode_attention / kivi_flush_residual
  * Errors: INVALID_ARG (also: a ring is full, no capacity left for the flush), UNSUPPORTED,
