@@ -225,13 +225,16 @@ __device__ __forceinline__ void key_tile_mfma(const uint32_t* w, const __half* b
 
 // Write the value-side small operand of one tile (lane -> token lane/2, channel groups
 // (lane%2)*2 + {0,1}) and accumulate the z-term  sum_t p_t z_t,g.
-template <int BITS, int REP>
+// MASKED: only the tile's first n_valid tokens are quantised values (a tile that also holds fp16
+// rows); otherwise every token counts -- slots past the end of an all-quantised chunk need no mask,
+// the softmax has set their probabilities to 0 and their (re-read) scales are finite.
+template <int BITS, int REP, bool MASKED>
 __device__ __forceinline__ void stage_value_operand(__half* bw, __half2 s2, __half2 z2, int n_valid,
                                                     const float (*lr)[kWaveTokens], int slot,
                                                     float (&zacc)[REP][2], int lane) {
     constexpr int NC = 2 * REP;
     const int t = lane >> 1, cg0 = (lane & 1) * 2;
-    const bool valid = t < n_valid;
+    const bool valid = !MASKED || t < n_valid;
     const float pf = inv_pos_factor<BITS>((t >> 1) & 3);
     const float s0 = valid ? __low2float(s2) * pf : 0.f, s1 = valid ? __high2float(s2) * pf : 0.f;
     const float z0 = valid ? __low2float(z2) : 0.f, z1 = valid ? __high2float(z2) : 0.f;
@@ -895,7 +898,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                     const int64_t so = (ubase + wave + 4 * i) * kTileTokens * 4 + 2 * lane;
                     const __half2 s2 = *reinterpret_cast<const __half2*>(p.v_scale + so);
                     const __half2 z2 = *reinterpret_cast<const __half2*>(p.v_zero + so);
-                    stage_value_operand<BITS, REP>(wl.b, s2, z2, n_vq_here, wl.lr, i, zacc, lane);
+                    stage_value_operand<BITS, REP, true>(wl.b, s2, z2, n_vq_here, wl.lr, i, zacc, lane);
                     wave_lds_sync();
                     value_tile_mfma<BITS, REP>(w, wl.b, acc, lane);
                     wave_lds_sync();
@@ -1015,8 +1018,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             for (int c0 = 0; c0 < kSlots; c0 += SS) {
 #pragma unroll
                 for (int s = 0; s < SS; ++s)
-                    stage_value_operand<BITS, REP>(wl.b + s * WL::kVSlot, vs2[c0 + s], vz2[c0 + s],
-                                                   c0 + s < cnt ? kTileTokens : 0, wl.lr, c0 + s, zacc, lane);
+                    stage_value_operand<BITS, REP, false>(wl.b + s * WL::kVSlot, vs2[c0 + s], vz2[c0 + s],
+                                                          kTileTokens, wl.lr, c0 + s, zacc, lane);
                 wave_lds_sync();
 #pragma unroll
                 for (int s = 0; s < SS; ++s) {
