@@ -155,3 +155,31 @@ def queries(w: Workload, step: int = 0) -> np.ndarray:
         for hq in range(w.n_q_heads):
             out[b, hq] = query_head(w, b, hq, step)
     return out
+
+
+ADVERSARIAL_KINDS = ("normal", "offset", "lattice", "lattice_offset", "tiny", "half_integers", "wide")
+
+
+def adversarial_values(kind: str, seed: int, shape) -> np.ndarray:
+    """fp16 inputs that stress a group-wise quantiser: plain normal data; a large offset with a small
+    spread (|min / scale| large); values on coarse lattices, which put many quotients exactly on or
+    next to rounding ties; ranges so small that the fp16 scale is subnormal; ranges near the top of
+    fp16.  Seeded; no arithmetic of the method in here."""
+    rng = np.random.Generator(np.random.PCG64([seed, ADVERSARIAL_KINDS.index(kind)]))
+    if kind == "normal":
+        x = rng.standard_normal(shape, dtype=np.float32)
+    elif kind == "offset":
+        x = 100.0 + 0.05 * rng.standard_normal(shape, dtype=np.float32)
+    elif kind == "lattice":
+        x = rng.integers(-12, 13, size=shape).astype(np.float32) / 8.0
+    elif kind == "lattice_offset":
+        x = 3.0 + rng.integers(0, 7, size=shape).astype(np.float32) / 2.0
+    elif kind == "tiny":
+        x = rng.integers(0, 9, size=shape).astype(np.float32) * np.float32(2.0 ** -24)
+    elif kind == "half_integers":
+        x = rng.integers(0, 31, size=shape).astype(np.float32) * 0.5
+    elif kind == "wide":
+        x = rng.standard_normal(shape, dtype=np.float32) * 3000.0
+    else:
+        raise ValueError(kind)
+    return x.astype(np.float16)

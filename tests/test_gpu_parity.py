@@ -226,3 +226,27 @@ def test_random_shapes(seed):
     print(f"case random seed={seed} b={w.batch} kv={n_kv} rep={rep} bits={w.bits} G={group} R={residual} "
           f"L={length} policy={policy} path={path} heads={heads}", flush=True)
     _run_case(w, length, policy, path, heads=heads)
+
+
+@pytest.mark.parametrize("group", [32, 128])
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("kind", workloads.ADVERSARIAL_KINDS)
+def test_quantise_adversarial_inputs(kind, bits, group):
+    """Codes, scales and zero-points bit-exact on inputs chosen against the quantise kernels' fast
+    path (one multiply-add per code with an exact redo next to rounding ties): lattices full of exact
+    ties, large |zero-point / scale|, subnormal fp16 scales, ranges near the top of fp16."""
+    torch = gh.require_gpu()
+    b, h, T = 2, 3, 1024
+    k = workloads.adversarial_values(kind, 11, (b, h, T, 128))
+    v = workloads.adversarial_values(kind, 12, (b, h, T, 128))
+    print(f"case adversarial {kind} bits={bits} G={group}", flush=True)
+    layout = kivi.make_layout(b, h, h, bits, 128, T, 288, group=group)
+    cache = kivi.Cache(layout)
+    kivi.kivi_quantize_key_groups(layout, torch.from_numpy(k).cuda(), T, cache)
+    kivi.kivi_quantize_value_tokens(layout, torch.from_numpy(v).cuda(), T, cache)
+    torch.cuda.synchronize()
+    oc = ko.StreamingCache(b, h, 128, bits, group, 0, "window")
+    oc.k_codes, oc.k_scale, oc.k_zero = ko.quantize_key(k, bits, group)
+    oc.v_codes, oc.v_scale, oc.v_zero = ko.quantize_value(v, bits, group)
+    oc.k_resid, oc.v_resid = k[:, :, :0], v[:, :, :0]
+    gh.compare_quantized_state(cache, oc)
