@@ -10,6 +10,8 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
+from paper_2402_02750_amd import workloads
+
 from oracle import kivi_oracle as ko
 
 
@@ -72,6 +74,27 @@ def test_range_and_error_bound(bits, kind):
     # interior codes obey the plain s/2 bound (no clamp involved)
     interior = (codes > 0) & (codes < levels) & nonconst[:, None]
     assert (err[interior] <= (s64 * (0.5 + 1e-6) * np.ones_like(err))[interior]).all()
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("kind", workloads.ADVERSARIAL_KINDS)
+def test_error_bound_on_adversarial_inputs(bits, kind):
+    """The same bound on the inputs the GPU parity test uses against the quantise kernels' fast
+    path (ties, large offsets, subnormal scales, wide ranges): the oracle itself must be right there."""
+    x = workloads.adversarial_values(kind, 11, (200, 32))
+    codes, s, z = ko.quantize_groups(x, bits)
+    levels = 2 ** bits - 1
+    assert codes.min() >= 0 and codes.max() <= levels
+    s64 = s.astype(np.float64)[:, None]
+    err = np.abs(ko.dequantize_groups(codes, s, z) - x.astype(np.float64))
+    normal = s64[:, 0] >= 2.0 ** -14                    # a normal fp16 scale: the relative clamp term applies
+    bound = s64 * (0.5 + 1e-6) + levels * 2.0 ** -11 * s64
+    assert (err[normal] <= bound[normal]).all()
+    assert np.array_equal(z, x.min(axis=1))
+    # minimum -> code 0, maximum -> top code wherever the group is not constant and s is normal
+    rows = np.flatnonzero(normal & (s64[:, 0] > 0))
+    assert (codes[rows, x[rows].argmin(axis=1)] == 0).all()
+    assert (codes[rows, x[rows].argmax(axis=1)] == levels).all()
 
 
 @pytest.mark.parametrize("bits", [2, 4])
