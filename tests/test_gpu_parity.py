@@ -205,7 +205,7 @@ def test_probability_accuracy_with_one_hot_values(path, bits):
     assert np.abs(out[big] / ref[big] - 1).max() < 5e-5
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(36))
 def test_random_shapes(seed):
     """Seeded random layouts (batch, heads, query heads per kv-head, bits, G, R, context length,
     policy, kernel family): the work partition, the part merging and the fp16 / quantised split
@@ -214,13 +214,13 @@ def test_random_shapes(seed):
     rng = np.random.default_rng(9000 + seed)
     group = int(rng.choice([32, 32, 64, 128]))
     residual = group * int(rng.integers(0, 256 // group + 1))
-    rep = int(rng.choice([1, 1, 2, 4, 8]))
+    rep = int(rng.choice([1, 1, 2, 3, 4, 8, 12]))
     n_kv = int(rng.integers(1, 6))
     w = scaled(CONFIGS["llama7b"], name=f"rand{seed}", batch=int(rng.integers(1, 6)), n_q_heads=n_kv * rep,
                n_kv_heads=n_kv, bits=int(rng.choice([2, 4])), group=group, residual=residual, seed=12000 + seed)
     length = int(rng.choice([rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 9000)]))
     policy = kivi.KIVI_FLUSH_WINDOW if residual == 0 or rng.integers(0, 2) else kivi.KIVI_FLUSH_ALG1
-    path = PATHS[int(rng.integers(0, 2))]
+    path = PATHS[int(rng.integers(0, len(PATHS)))]
     all_heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
     heads = [all_heads[i] for i in rng.choice(len(all_heads), size=min(3, len(all_heads)), replace=False)]
     print(f"case random seed={seed} b={w.batch} kv={n_kv} rep={rep} bits={w.bits} G={group} R={residual} "
