@@ -82,8 +82,10 @@ extern "C" {
 #define KIVI_DECODE_MFMA_ONE    3   /* ... always as one launch                                      */
 #define KIVI_DECODE_MFMA_TWO    4   /* ... as two launches where the cache has both quantised tokens */
                                     /* and fp16 rows: the fp16 rows first, then the quantised part   */
-                                    /* (KIVI_DECODE_MFMA and AUTO take two launches when a workgroup */
-                                    /* would otherwise own several (batch, kv-head) units)           */
+                                    /* (KIVI_DECODE_MFMA and AUTO pick the form from the shape: two  */
+                                    /* launches when a workgroup would otherwise own parts of several*/
+                                    /* (batch, kv-head) units, or with 3 or more query heads per     */
+                                    /* kv-head and enough fp16 rows; kivi_decode_plan tells which)   */
 
 /* Static description of one attention layer's cache (host struct). */
 typedef struct kivi_layout {
@@ -223,7 +225,7 @@ int kivi_decode_attention(const kivi_layout_t* layout, const kivi_cache_t* cache
  * parts, flush them per `policy`, attention of t_Q over the updated cache -- in as few launches
  * as possible.  The result is the same as kivi_append_residual + kivi_flush_residual +
  * kivi_decode_attention.  On steps where nothing is flushed and the matrix-core family runs, the
- * append costs no launch of its own: the attention (one launch, or two on large batches, see
+ * append costs no launch of its own: the attention (one launch or two, see
  * kivi_decode_plan) reads the new token's rows from k_new / v_new and writes them into the
  * residual rings itself.  On the other steps it enqueues the separate kernels.
  *   k_new, v_new   device, fp16 [b][n_kv_heads][128]; they must stay valid until the launch has run

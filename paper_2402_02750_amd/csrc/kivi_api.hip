@@ -179,24 +179,44 @@ int decode_family(const kivi_layout_t* l) {
 }
 
 // The matrix-core family as two launches (fp16 rows first, then the all-quantised chunks): possible
-// when the cache has both parts and K and V are split at the same token; chosen when asked for,
-// or when a workgroup of the persistent kernel would own several (batch, kv-head) units -- their
-// fp16-row chunks would then run one after the other, each a chain of dependent steps.
+// when the cache has both parts and K and V are split at the same token; chosen when asked for, or
+// by three measured rules.
+//  (1) A workgroup of the persistent kernel would own several (batch, kv-head) units: their fp16-row
+//      chunks would run one after the other, each a chain of dependent steps (32 heads, context 4096,
+//      2 bits: equal at 1 unit per workgroup, 4-6 % faster from 1.5 on).
+//  (2) Between half a unit and one unit per workgroup most workgroups straddle two units and run two
+//      such chains: two launches are 2-12 % faster once the launch is long enough to carry the
+//      second launch's fixed 8-12 us.
+//  (3) Fewer units still, but 3 or more query heads per kv-head and at least two tiles of fp16 rows:
+//      the rows of a unit cost the persistent kernel more than their weight on its cost axis (and
+//      the 4-bit instantiation for 5 to 8 heads spills registers in the single-launch form only).
+//      Two launches pay from a total amount of work (units x tiles) and of fp16-row work
+//      (units x fp16 tiles) on.
+// The thresholds are fitted to sweeps over 8-4096 units, contexts 1k-16k, windows 32-192, 1-8 heads
+// per kv-head, 2 and 4 bits (730 shapes): against the better form of each shape these rules lose
+// 0.3-1.2 % on average per instantiation, a single launch everywhere 1.4-15 %.
 bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path) {
     if (path != KIVI_DECODE_MFMA || l->decode_path == KIVI_DECODE_MFMA_ONE) return false;
     const int rep_launch = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
     const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
-    const int tiles_b = ceil_div(c->n_kq + c->n_kr, kTileTokens) - c->n_kq / kTileTokens;
+    const int tiles_total = ceil_div(c->n_kq + c->n_kr, kTileTokens);
+    const int tiles_b = tiles_total - c->n_kq / kTileTokens;
     const bool possible = c->n_kq == c->n_vq && c->n_kq >= kTileTokens && c->n_kr > 0 &&
                           residual_rows_possible(tiles_b, rep_variant);
+    if (!possible) return false;
+    if (l->decode_path == KIVI_DECODE_MFMA_TWO) return true;
     const int64_t units = (int64_t)l->batch * l->n_kv_heads;
     const int resident = mfma_geometry(l->bits, rep_launch).resident_workgroups;
-    // (measured at 32 heads, context 4096, 2 bits: equal at 1 unit per workgroup, 4-6 % faster from 1.5 on)
-    // The 4-bit instantiation for 5 to 8 query heads per kv-head spills registers in its single-launch
-    // form and not in the other: two launches there at every size measured (16 to 128 units:
-    // 89 -> 75, 83 -> 69, 123 -> 87 us).
-    const bool spilling = rep_variant == 8 && l->bits == 4;
-    return possible && (l->decode_path == KIVI_DECODE_MFMA_TWO || spilling || units * 4 >= (int64_t)resident * 5);
+    const int64_t work = units * tiles_total, row_work = units * tiles_b;
+    if (units * 4 >= (int64_t)resident * 5) return true;                                             // (1)
+    if (units * 2 > resident && units < resident && tiles_b >= 2 && work >= 24000) return true;      // (2)
+    if (rep_variant < 4) return false;
+    int64_t min_work, min_row_work;                                                                  // (3)
+    int min_tiles_b = 2;
+    if (rep_variant == 8) { min_work = 4000; min_row_work = l->bits == 4 ? 128 : 384; }
+    else if (l->bits == 4) { min_work = 8000; min_row_work = 256; }
+    else { min_work = 16000; min_row_work = 512; min_tiles_b = 3; }
+    return tiles_b >= min_tiles_b && work >= min_work && row_work >= min_row_work;
 }
 
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the

@@ -233,8 +233,20 @@ def test_decode_plan(lib):
     assert plan(64, 32, 32, 2, 0, 100, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 1
     assert plan(64, 32, 32, 2, 1920, 0, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 1
     assert plan(64, 32, 32, 2, 1920, 150, n_vq=1984, n_vr=86).launches == 1
-    # 4-bit, 8 query heads per kv-head: two launches at any size
-    assert plan(2, 64, 8, 4, 4096, 128).launches == 2
+    # 4 or more query heads per kv-head, fewer units than workgroups: two launches once there is
+    # enough work overall and enough fp16 rows, one launch below that and for a one-tile window
+    assert plan(8, 64, 8, 4, 4096, 128).launches == 2        # 64 units x 132 tiles, 256 fp16 tiles
+    assert plan(1, 64, 8, 4, 4096, 128).launches == 1        # 8 units: too little work
+    assert plan(32, 64, 8, 2, 3968, 128).launches == 2       # 2-bit, 8 heads: 256 units x 4 fp16 tiles
+    assert plan(8, 64, 8, 2, 3968, 128).launches == 1        # ... 64 units x 4 fp16 tiles: one launch
+    assert plan(32, 64, 8, 2, 4064, 32).launches == 1        # a single tile of fp16 rows
+    assert plan(8, 32, 8, 2, 3968, 128).launches == 1        # 2-bit, 4 heads: 64 units x 128 tiles is little work
+    assert plan(48, 32, 8, 2, 3968, 128).launches == 2
+    # 1 head per kv-head: only by units per workgroup -- more than one, or between a half and one
+    # (workgroups straddle two units) in a launch long enough to carry a second one
+    assert plan(32, 8, 8, 2, 3968, 128).launches == 1        # 256 units: two workgroups per unit
+    assert plan(48, 8, 8, 2, 3968, 128).launches == 2        # 384 units x 128 tiles
+    assert plan(48, 8, 8, 2, 992, 128).launches == 1         # 384 units x 35 tiles: too short
     assert plan(2, 64, 8, 2, 4096, 128).launches == 1
     # vector-ALU family: decode + merge
     p = plan(16, 32, 32, 2, 3968, 128, path=kivi.KIVI_DECODE_VALU)
