@@ -188,13 +188,13 @@ int decode_family(const kivi_layout_t* l) {
 //      such chains: two launches are 2-12 % faster once the launch is long enough to carry the
 //      second launch's fixed 8-12 us.
 //  (3) Fewer units still, but 3 or more query heads per kv-head and at least two tiles of fp16 rows:
-//      the rows of a unit cost the persistent kernel more than their weight on its cost axis (and
-//      the 4-bit instantiation for 5 to 8 heads spills registers in the single-launch form only).
-//      Two launches pay from a total amount of work (units x tiles) and of fp16-row work
-//      (units x fp16 tiles) on.
-// The thresholds are fitted to sweeps over 8-4096 units, contexts 1k-16k, windows 32-192, 1-8 heads
-// per kv-head, 2 and 4 bits (730 shapes): against the better form of each shape these rules lose
-// 0.3-1.2 % on average per instantiation, a single launch everywhere 1.4-15 %.
+//      the rows kernel runs every tile of every unit at once where the persistent kernel gives each
+//      fp16-row chunk to one workgroup (and its 4-bit instantiation for 5 to 8 heads spills
+//      registers in the single-launch form only).  Two launches pay from a total amount of work
+//      (units x tiles) and of fp16-row work (units x fp16 tiles) on.
+// The thresholds are fitted to sweeps of both forms over 8-4096 units, contexts 1k-16k, windows
+// 32-192, 1-8 heads per kv-head, 2 and 4 bits (730 shapes): against the better form of each shape
+// these rules lose 0.1-1.2 % on average per instantiation, a single launch everywhere 1.3-7.6 %.
 bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path) {
     if (path != KIVI_DECODE_MFMA || l->decode_path == KIVI_DECODE_MFMA_ONE) return false;
     const int rep_launch = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
@@ -213,9 +213,8 @@ bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path)
     if (rep_variant < 4) return false;
     int64_t min_work, min_row_work;                                                                  // (3)
     int min_tiles_b = 2;
-    if (rep_variant == 8) { min_work = 4000; min_row_work = l->bits == 4 ? 128 : 384; }
-    else if (l->bits == 4) { min_work = 8000; min_row_work = 256; }
-    else { min_work = 16000; min_row_work = 512; min_tiles_b = 3; }
+    if (rep_variant == 8) { min_work = 4000; min_row_work = 384; }
+    else { min_work = l->bits == 4 ? 10000 : 16000; min_row_work = 512; min_tiles_b = 3; }
     return tiles_b >= min_tiles_b && work >= min_work && row_work >= min_row_work;
 }
 

@@ -1058,10 +1058,17 @@ hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
     const int64_t units = (int64_t)p.batch * p.n_kv_heads;
     const int64_t total_a = units * p.plan.n_splits_a, total_b = units * p.plan.n_splits_b;
-    // cost of an fp16-row chunk in units of an all-quantised chunk: by the bytes they stream
+    // Cost of an fp16-row chunk in units of an all-quantised chunk: by the bytes they stream, times
+    // a measured factor per instantiation -- with 5 to 8 query heads per kv-head, and with 3 or 4 at
+    // 4 bits, the chain  rows -> logits -> softmax -> rows -> outputs  of an fp16-row chunk takes about
+    // as long as two all-quantised chunks (sweep of the weight from 1 to 5 over 8-512 units, contexts
+    // 1k-16k, windows 64-192: 2 is best for all three, 2-7 % on average and up to 36 % faster than 1;
+    // odd weights leave workgroups with an fp16-row chunk and all-quantised chunks and are slower).
+    // One head or two, and 3 or 4 heads at 2 bits: 1.
+    constexpr int kRowsFactor = (REP > 4 || (REP > 2 && BITS == 4)) ? 2 : 1;
     const int64_t bytes_a = (int64_t)4 * SLOTS * kTileTokens * 2 * (kHeadDim * BITS / 8 + 16);
     const int64_t bytes_b = (int64_t)p.plan.tiles_per_split_b * kTileTokens * 2 * kHeadDim * 2;
-    p.cost_b = (int)std::max<int64_t>(1, (bytes_b + bytes_a / 2) / bytes_a);
+    p.cost_b = kRowsFactor * (int)std::max<int64_t>(1, (bytes_b + bytes_a / 2) / bytes_a);
     p.cost_unit = p.plan.n_splits_b * p.cost_b + p.plan.n_splits_a;
     p.total_cost = units * p.cost_unit;
     if (p.total_cost <= 0 || p.total_cost > 0x3fffffff || total_a + total_b > 0x7fffffff) return hipErrorInvalidValue;

@@ -235,7 +235,8 @@ def test_decode_plan(lib):
     assert plan(64, 32, 32, 2, 1920, 150, n_vq=1984, n_vr=86).launches == 1
     # 4 or more query heads per kv-head, fewer units than workgroups: two launches once there is
     # enough work overall and enough fp16 rows, one launch below that and for a one-tile window
-    assert plan(8, 64, 8, 4, 4096, 128).launches == 2        # 64 units x 132 tiles, 256 fp16 tiles
+    assert plan(16, 64, 8, 4, 4096, 128).launches == 2       # 128 units x 132 tiles, 512 fp16 tiles
+    assert plan(8, 64, 8, 4, 4096, 128).launches == 1        # 64 units: 256 fp16 tiles are too few
     assert plan(1, 64, 8, 4, 4096, 128).launches == 1        # 8 units: too little work
     assert plan(32, 64, 8, 2, 3968, 128).launches == 2       # 2-bit, 8 heads: 256 units x 4 fp16 tiles
     assert plan(8, 64, 8, 2, 3968, 128).launches == 1        # ... 64 units x 4 fp16 tiles: one launch

@@ -14,6 +14,7 @@ from paper_2402_02750_amd.workloads import CONFIGS, scaled
 pytestmark = pytest.mark.gpu
 
 PATHS = [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA, kivi.KIVI_DECODE_MFMA_TWO]
+RANDOM_PATHS = PATHS + [kivi.KIVI_DECODE_MFMA_ONE]
 PATH_IDS = ["valu", "mfma", "mfma2"]
 
 
@@ -205,6 +206,23 @@ def test_probability_accuracy_with_one_hot_values(path, bits):
     assert np.abs(out[big] / ref[big] - 1).max() < 5e-5
 
 
+@pytest.mark.parametrize("bits,rep", [(2, 8), (2, 5), (4, 3), (4, 4), (4, 8)])
+@pytest.mark.parametrize("batch,n_kv,length,residual", [(1, 2, 1500, 128), (3, 8, 4200, 128), (2, 5, 700, 192),
+                                                        (40, 8, 1100, 96), (70, 8, 600, 64)])
+def test_single_launch_weighted_rows(bits, rep, batch, n_kv, length, residual):
+    """The single-launch form on the instantiations whose fp16-row chunks weigh two all-quantised
+    chunks on the work axis: from fewer chunks than workgroups (every chunk a workgroup of its
+    own, a unit's parts merged over a dozen workgroups) to workgroups that own parts of several
+    units."""
+    w = scaled(CONFIGS["llama7b"], name="rows2", batch=batch, n_q_heads=n_kv * rep, n_kv_heads=n_kv, bits=bits,
+               residual=residual, seed=500 + bits + rep)
+    rng = np.random.default_rng(batch * 131 + n_kv)
+    all_heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    heads = [all_heads[i] for i in rng.choice(len(all_heads), size=min(3, len(all_heads)), replace=False)]
+    print(f"case single-launch rows bits={bits} rep={rep} b={batch} kv={n_kv} L={length} R={residual} heads={heads}", flush=True)
+    _run_case(w, length, kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_DECODE_MFMA_ONE, heads=heads)
+
+
 @pytest.mark.parametrize("seed", range(36))
 def test_random_shapes(seed):
     """Seeded random layouts (batch, heads, query heads per kv-head, bits, G, R, context length,
@@ -220,7 +238,7 @@ def test_random_shapes(seed):
                n_kv_heads=n_kv, bits=int(rng.choice([2, 4])), group=group, residual=residual, seed=12000 + seed)
     length = int(rng.choice([rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 9000)]))
     policy = kivi.KIVI_FLUSH_WINDOW if residual == 0 or rng.integers(0, 2) else kivi.KIVI_FLUSH_ALG1
-    path = PATHS[int(rng.integers(0, len(PATHS)))]
+    path = RANDOM_PATHS[int(rng.integers(0, len(RANDOM_PATHS)))]
     all_heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
     heads = [all_heads[i] for i in rng.choice(len(all_heads), size=min(3, len(all_heads)), replace=False)]
     print(f"case random seed={seed} b={w.batch} kv={n_kv} rep={rep} bits={w.bits} G={group} R={residual} "
