@@ -85,3 +85,37 @@ def test_decode_step_matches_oracle(path, policy, bits, rep, group):
     torch.cuda.synchronize()
     gh.compare_quantized_state(cache, oc)
     print(f"decode_step worst abs err {worst:.3e}", flush=True)
+
+
+def test_decode_step_launch_form_changes_between_steps():
+    """A batch on the automatic choice whose attention changes form from step to step: one launch
+    right after a flush (a one-tile window), two launches once the window has grown into a second
+    tile.  Both forms must leave the cache and the workspace as the other one expects them; two
+    sequences of the batch are followed by the oracle."""
+    torch = gh.require_gpu()
+    rep, bits, policy = 8, 2, kivi.KIVI_FLUSH_WINDOW
+    w = scaled(CONFIGS["stream"], name="form_flip", batch=24, n_q_heads=8 * rep, n_kv_heads=8, bits=bits,
+               group=32, residual=32, prompt=690, decode_steps=70, seed=31337)
+    total = w.prompt + w.decode_steps
+    k, v = workloads.keys(w, total), workloads.values(w, total)
+    print("case decode_step form flip", flush=True)
+    layout, cache = gh.gpu_prefill(w, k[:, :, :w.prompt], v[:, :, :w.prompt], policy, kivi.KIVI_DECODE_AUTO,
+                                   extra_q_tokens=w.decode_steps)
+    sel = [3, 17]
+    oc = ko.StreamingCache(len(sel), w.n_kv_heads, 128, bits, w.group, w.residual, "window")
+    oc.prefill(k[sel, :, :w.prompt], v[sel, :, :w.prompt])
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    out = torch.empty(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    forms, worst = set(), 0.0
+    for step in range(w.decode_steps):
+        t = w.prompt + step
+        q = workloads.queries(w, step)
+        kivi.kivi_decode_step(layout, cache, kt[:, :, t].contiguous(), vt[:, :, t].contiguous(),
+                              torch.from_numpy(q).cuda(), w.softmax_scale, out, policy)
+        forms.add(kivi.kivi_decode_plan(layout, cache).launches)      # the form this step's attention took
+        oc.append(k[sel, :, t], v[sel, :, t])
+        torch.cuda.synchronize()
+        assert (cache.c.n_kq, cache.c.n_kr) == (oc.n_kq, oc.n_kr), f"step {step}"
+        worst = max(worst, gh.check_close(out.cpu().numpy()[sel], oc.attention(q[sel], w.softmax_scale), f"step {step}"))
+    assert forms == {1, 2}, forms
+    print(f"form flip worst abs err {worst:.3e}", flush=True)
