@@ -51,9 +51,10 @@ int check_source(const void* x, int64_t sb, int64_t sh, int64_t st) {
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// The workspace starts with one finished-split counter per (batch, kv-head), padded to 256 bytes.
+// The workspace starts with two finished-split counters per (batch, kv-head) -- one per half of the
+// kv-head's query heads, should a launch serve the halves as units of their own -- padded to 256 bytes.
 size_t counter_bytes(const kivi_layout_t* l) {
-    return ((size_t)l->batch * l->n_kv_heads * sizeof(int32_t) + 255) / 256 * 256;
+    return ((size_t)l->batch * l->n_kv_heads * 2 * sizeof(int32_t) + 255) / 256 * 256;
 }
 
 // Upper bound of the number of context splits for any cache state of this layout.
@@ -218,6 +219,22 @@ bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path)
     return tiles_b >= min_tiles_b && work >= min_work && row_work >= min_row_work;
 }
 
+// With 6 or 8 query heads per kv-head and few chunks per workgroup the single launch lasts about as
+// long as its chunks, and a chunk takes twice as long with 8 heads as with 4 (8 kv-heads, context
+// 4096, batch 1: 15 us with 4 heads per kv-head, 30 us with 8).  Then the two halves of every group run
+// as units of their own on the 4-head instantiation: twice the workgroups, each half as long; the
+// cache is read twice, which such launches do not notice.  Measured (8 kv-heads, batch 1-32, contexts
+// 1k-32k): faster wherever there are up to 4 chunks per resident workgroup at 2 bits (30.5 -> 18.3 us
+// at batch 1 / context 4096, 69.6 -> 46.8 us at batch 2 / 32k; mixed beyond) and up to 16 at 4 bits,
+// whose 8-head instantiation spills registers (29.5 -> 18.9, 98.5 -> 81.9 us).
+bool wants_head_split(const kivi_layout_t* l, const SplitPlan& plan, int path, bool two_launches) {
+    const int rep_total = l->n_q_heads / l->n_kv_heads;
+    if (path != KIVI_DECODE_MFMA || two_launches || (rep_total != 6 && rep_total != 8)) return false;
+    const int64_t chunks = (int64_t)l->batch * l->n_kv_heads * plan.n_splits();
+    const int max_chunks_per_workgroup = l->bits == 4 ? 16 : 4;
+    return chunks <= (int64_t)mfma_geometry(l->bits, 4).resident_workgroups * max_chunks_per_workgroup;
+}
+
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the
 // rows of token length-1 are not in the rings yet and the (matrix-core) kernel puts them there.
 int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, float softmax_scale,
@@ -259,6 +276,13 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     // matrix-core kernel leaves its counters at zero).  Only the first one appends the new token.
     const int rep_total = l->n_q_heads / l->n_kv_heads;
     p.rep_variant = std::min(rep_total, kMaxRep);
+    if (wants_head_split(l, p.plan, path, two)) {
+        p.head_split = 1;
+        p.rep_variant = 4;
+        p.q_head0 = 0;
+        p.rep_here = rep_total / 2;
+        return hip_status(launch_decode_mfma(p, hs));
+    }
     for (int h0 = 0; h0 < rep_total; h0 += kMaxRep) {
         p.q_head0 = h0;
         p.rep_here = std::min(kMaxRep, rep_total - h0);
@@ -338,6 +362,7 @@ int kivi_decode_plan(const kivi_layout_t* l, const kivi_cache_t* c, kivi_decode_
     const SplitPlan plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
     out->family = path;
     out->launches = path == KIVI_DECODE_MFMA ? (two ? 2 : 1) : 2;       // vector-ALU family: decode + merge
+    out->units_per_kv_head = wants_head_split(l, plan, path, two) ? 2 : 1;
     out->splits_quantised = plan.n_splits_a;
     out->splits_fp16 = plan.n_splits_b;
     out->tiles_per_split_quantised = plan.tiles_per_split_a;

@@ -276,7 +276,7 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
 // first launch into it.
 constexpr int kBothPhases = 0, kQuantisedOnly = 1;
 
-template <int BITS, int REP, int SLOTS, int OCC, int MODE>
+template <int BITS, int REP, int SLOTS, int OCC, int MODE, bool HSPLIT = false>
 __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     constexpr int kSlots = SLOTS;
     // tile slots staged at once: two where that divides the slots and the registers allow
@@ -314,6 +314,14 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
     // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
     const int rep = p.rep_here, rep_total = p.n_q_heads / p.n_kv_heads;
+    // HSPLIT: a unit of the work axis is (batch, kv-head, half of the kv-head's query heads) -- unit u
+    // reads the cache of (batch, kv-head) u / 2 and serves the query heads (u & 1) * rep .. + rep of
+    // its group; parts, counters and held results go by u.
+    auto kv_unit = [&](int u) -> int { return HSPLIT ? u >> 1 : u; };
+    auto first_q_head = [&](int u) -> int {
+        return (kv_unit(u) % p.n_kv_heads) * rep_total + p.q_head0 + (HSPLIT ? (u & 1) * rep : 0);
+    };
+    auto batch_of = [&](int u) -> int { return kv_unit(u) / p.n_kv_heads; };
     // chunks per unit on this launch's cost axis: all-quantised / with fp16 rows
     const int n_a = p.plan.n_splits_a, n_b = MODE == kQuantisedOnly ? 0 : p.plan.n_splits_b;
     const int cpu = p.plan.n_splits_a + p.plan.n_splits_b;       // workspace rows per (batch, query head)
@@ -376,7 +384,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         j_phys -= j_phys >= nx_lo + nx_len ? nx_len : 0;
         const int tile0 = j_phys * p.plan.tiles_per_split_a;
         nx_nt = min(p.plan.tiles_per_split_a, p.plan.tiles_a - tile0);
-        nx_base = (int64_t)nx_u * p.cap_tiles + tile0;
+        nx_base = (int64_t)kv_unit(nx_u) * p.cap_tiles + tile0;
     };
     auto chunk_tile = [&](int slot_or_row) -> int64_t { return nx_base + min(wave + 4 * slot_or_row, nx_nt - 1); };
     // Requests for the "next" all-quantised chunk.  They are issued unconditionally so that the
@@ -446,8 +454,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     };
     __half q_pre[kIdx];
     auto request_q = [&](int u) {
-        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
-        const int b = u / p.n_kv_heads;
+        const int hq0 = first_q_head(u);
+        const int b = batch_of(u);
 #pragma unroll
         for (int k = 0; k < kIdx; ++k) {
             const int idx = min(tid + 256 * k, rep * kHeadDim - 1);        // unconditional loads (clamped)
@@ -456,8 +464,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     };
     float pre_m[kIdx], pre_l[kIdx], pre_o[kIdx];
     auto request_rows_part = [&](int u) {
-        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
-        const int b = u / p.n_kv_heads;
+        const int hq0 = first_q_head(u);
+        const int b = batch_of(u);
 #pragma unroll
         for (int k = 0; k < kIdx; ++k) {
             const int idx = min(tid + 256 * k, rep * kHeadDim - 1);        // unconditional loads (clamped)
@@ -472,8 +480,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // sole: single part, output written directly; hold_put >= 0: the part is parked in that LDS slot;
     // hold_get >= 0: the part parked in that slot is merged in and the output written directly.
     auto finish_unit = [&](int u, bool fp16_phase, bool sole, int hold_put, int hold_get) __attribute__((always_inline)) {
-        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
-        const int b = u / p.n_kv_heads;
+        const int hq0 = first_q_head(u);
+        const int b = batch_of(u);
         // raw matrix-core outputs: column n of acc[u8] -> lr[n][channel]
         if (n < NC) {
 #pragma unroll
@@ -653,8 +661,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 
     // ---- enter a unit: query operands ----
     auto enter_unit = [&](int u) {
-        const int hq0 = (u % p.n_kv_heads) * rep_total + p.q_head0;
-        const int b = u / p.n_kv_heads;
+        const int hq0 = first_q_head(u);
+        const int b = batch_of(u);
         auto stage = [&](int i, float x) {
             const int hh = i / kHeadDim, c = i % kHeadDim;
             __half hi, lo;
@@ -768,7 +776,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         for (int ck = b_lo; ck < b_hi; ++ck) {
             const int tile0 = p.plan.tiles_a + (ck - u * n_b) * p.plan.tiles_per_split_b;
             const int n_tiles = min(p.plan.tiles_per_split_b, p.plan.tiles_total - tile0);
-            const int64_t unit = u;
+            const int64_t unit = kv_unit(u);
             const bool fused_append = p.k_new != nullptr;
             const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;
             const int64_t ubase = unit * p.cap_tiles + tile0;
@@ -806,7 +814,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             __half* new_dst = nullptr;
             if (fused_append) {
                 const int last = p.length - 1, last_tile = last / kTileTokens;
-                owns_new = last_tile >= tile0 && last_tile < tile0 + n_tiles && ((last_tile - tile0) & 3) == wave && lane < 32;
+                owns_new = last_tile >= tile0 && last_tile < tile0 + n_tiles && ((last_tile - tile0) & 3) == wave && lane < 32 &&
+                           (!HSPLIT || (u & 1) == 0);      // the two halves of a kv-head would store the same rows
                 if (owns_new) {
                     const bool is_v = lane >= 16;
                     const int slot = is_v ? ring_slot(p.v_r_start, last - p.n_vq, p.cap_r)
@@ -843,7 +852,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                     // finished logit a is stored as a * 2^-24 in the head's hi column (lo column and
                     // z-term 0), which the softmax turns back into a exactly.
                     const int seg = lane & 15, row = lane >> 4;
-                    const int64_t qrow = ((int64_t)(u / p.n_kv_heads) * p.n_q_heads + (u % p.n_kv_heads) * rep_total + p.q_head0) * kHeadDim;
+                    const int64_t qrow = ((int64_t)batch_of(u) * p.n_q_heads + first_q_head(u)) * kHeadDim;
 #pragma unroll
                     for (int j0 = 0; j0 < 8; j0 += RB) {
                         half8 kr[RB];
@@ -1038,14 +1047,14 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 }
 
 // Workgroups the chip holds at once for one instantiation (occupancy query, cached).
-template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases>
+template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases, bool HSPLIT = false>
 int resident_workgroups() {
     static int cached = 0;
     if (cached == 0) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE>, 256, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE, HSPLIT>, 256, 0) != hipSuccess ||
             cus <= 0 || per_cu <= 0)
             return 256 * OCC;
         cached = cus * per_cu;
@@ -1053,10 +1062,10 @@ int resident_workgroups() {
     return cached;
 }
 
-template <int BITS, int REP, int SLOTS, int OCC>
+template <int BITS, int REP, int SLOTS, int OCC, bool HSPLIT = false>
 hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
-    const int64_t units = (int64_t)p.batch * p.n_kv_heads;
+    const int64_t units = (int64_t)p.batch * p.n_kv_heads * (HSPLIT ? 2 : 1);
     const int64_t total_a = units * p.plan.n_splits_a, total_b = units * p.plan.n_splits_b;
     // Cost of an fp16-row chunk in units of an all-quantised chunk: by the bytes they stream, times
     // a measured factor per instantiation -- with 5 to 8 query heads per kv-head, and with 3 or 4 at
@@ -1075,9 +1084,9 @@ hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     p.total_chunks_a = (int)total_a;
     p.total_chunks_b = (int)total_b;
     // every resident workgroup gets an equal share of the cost axis (within one unit of cost)
-    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC>(),
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kBothPhases, HSPLIT>(),
                                                                   p.total_cost / p.cost_b));
-    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kBothPhases><<<grid, 256, 0, stream>>>(p);
+    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kBothPhases, HSPLIT><<<grid, 256, 0, stream>>>(p);
     return hipGetLastError();
 }
 
@@ -1125,6 +1134,14 @@ bool with_variant(int bits, int rep_layout, F&& fn) {
 
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
+    if (p.head_split > 0) {
+        // the two halves of every kv-head's query heads as units of their own, on the 4-head instantiation
+        if (p.two_launches > 0 || p.rep_variant != 4 || p.q_head0 != 0 || 2 * p.rep_here != p.n_q_heads / p.n_kv_heads)
+            return hipErrorInvalidValue;
+        if (p.bits == 2) return launch_one<2, 4, 4, 2, true>(p, stream);
+        if (p.bits == 4) return launch_one<4, 4, 2, 2, true>(p, stream);
+        return hipErrorNotSupported;
+    }
     with_variant(p.bits, p.rep_variant, [&](auto v) {
         using V = decltype(v);
         e = p.two_launches > 0 ? launch_two<V::bits, V::rep, V::slots, V::occ>(p, stream)

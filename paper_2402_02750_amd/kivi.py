@@ -57,7 +57,8 @@ class kivi_seq_state_t(ctypes.Structure):
 
 class kivi_decode_plan_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("family", "launches", "splits_quantised", "splits_fp16",
-                                              "tiles_per_split_quantised", "tiles_per_split_fp16")]
+                                              "tiles_per_split_quantised", "tiles_per_split_fp16",
+                                              "units_per_kv_head")]
 
 
 class kivi_cache_sizes_t(ctypes.Structure):

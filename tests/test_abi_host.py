@@ -229,6 +229,14 @@ def test_decode_plan(lib):
     assert (p.family, p.launches, p.splits_fp16, p.tiles_per_split_fp16) == (kivi.KIVI_DECODE_MFMA, 2, 1, 5)
     assert plan(64, 32, 32, 2, 1920, 150, path=kivi.KIVI_DECODE_MFMA_ONE).launches == 1
     assert plan(16, 32, 32, 2, 3968, 128, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 2
+    # 6 or 8 query heads per kv-head and few chunks per workgroup: the halves of every group as units of their own
+    assert plan(1, 64, 8, 2, 3968, 128).units_per_kv_head == 2      # 8 units x 12 chunks
+    assert plan(1, 48, 8, 4, 3968, 128).units_per_kv_head == 2
+    assert plan(1, 56, 8, 2, 3968, 128).units_per_kv_head == 1      # 7 heads do not halve
+    assert plan(1, 32, 8, 2, 3968, 128).units_per_kv_head == 1      # 4 heads: nothing to split
+    assert plan(16, 64, 8, 2, 16256, 128).units_per_kv_head == 1    # 128 units x 36 chunks: too many at 2 bits
+    assert plan(32, 64, 8, 2, 3968, 128, path=kivi.KIVI_DECODE_MFMA_TWO).units_per_kv_head == 1
+    assert plan(1, 64, 8, 2, 3968, 128, path=kivi.KIVI_DECODE_VALU).units_per_kv_head == 1
     # two launches need both parts and K and V split at the same token
     assert plan(64, 32, 32, 2, 0, 100, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 1
     assert plan(64, 32, 32, 2, 1920, 0, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 1

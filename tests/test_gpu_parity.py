@@ -18,12 +18,14 @@ RANDOM_PATHS = PATHS + [kivi.KIVI_DECODE_MFMA_ONE]
 PATH_IDS = ["valu", "mfma", "mfma2"]
 
 
-def _run_case(w, length, policy, path, heads=None):
+def _run_case(w, length, policy, path, heads=None, units_per_kv_head=None):
     torch = gh.require_gpu()
     k = workloads.keys(w, length)
     v = workloads.values(w, length)
     q = workloads.queries(w)
     layout, cache = gh.gpu_prefill(w, k, v, policy, path)
+    if units_per_kv_head is not None:
+        assert kivi.kivi_decode_plan(layout, cache).units_per_kv_head == units_per_kv_head
     all_heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
     heads = all_heads if heads is None else heads
     oc = gh.oracle_cache_for_heads(w, k, v, heads, "window" if policy == kivi.KIVI_FLUSH_WINDOW else "alg1")
@@ -221,6 +223,22 @@ def test_single_launch_weighted_rows(bits, rep, batch, n_kv, length, residual):
     heads = [all_heads[i] for i in rng.choice(len(all_heads), size=min(3, len(all_heads)), replace=False)]
     print(f"case single-launch rows bits={bits} rep={rep} b={batch} kv={n_kv} L={length} R={residual} heads={heads}", flush=True)
     _run_case(w, length, kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_DECODE_MFMA_ONE, heads=heads)
+
+
+@pytest.mark.parametrize("path", [kivi.KIVI_DECODE_MFMA, kivi.KIVI_DECODE_MFMA_ONE], ids=["mfma", "mfma1"])
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("rep", [6, 8])
+@pytest.mark.parametrize("batch,n_kv,length,residual,policy", [
+    (1, 8, 1500, 128, kivi.KIVI_FLUSH_WINDOW), (3, 2, 5000, 128, kivi.KIVI_FLUSH_WINDOW),
+    (2, 8, 700, 32, kivi.KIVI_FLUSH_ALG1), (5, 3, 333, 64, kivi.KIVI_FLUSH_WINDOW), (1, 1, 40, 32, kivi.KIVI_FLUSH_WINDOW)])
+def test_query_head_halves_as_units(path, bits, rep, batch, n_kv, length, residual, policy):
+    """Small batches with 6 or 8 query heads per kv-head: the two halves of every group are units of
+    their own on the 4-head instantiation (the plan says so), each reading the kv-head's cache --
+    one unit spread over many workgroups, several units in one workgroup, fp16 rows only."""
+    w = scaled(CONFIGS["llama7b"], name="halves", batch=batch, n_q_heads=n_kv * rep, n_kv_heads=n_kv, bits=bits,
+               residual=residual, seed=900 + bits + rep)
+    print(f"case head halves path={path} bits={bits} rep={rep} b={batch} kv={n_kv} L={length} R={residual}", flush=True)
+    _run_case(w, length, policy, path, units_per_kv_head=2)
 
 
 @pytest.mark.parametrize("seed", range(36))
