@@ -219,18 +219,27 @@ bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path)
     return tiles_b >= min_tiles_b && work >= min_work && row_work >= min_row_work;
 }
 
-// With 6 or 8 query heads per kv-head and few chunks per workgroup the single launch lasts about as
-// long as its chunks, and a chunk takes twice as long with 8 heads as with 4 (8 kv-heads, context
-// 4096, batch 1: 15 us with 4 heads per kv-head, 30 us with 8).  Then the two halves of every group run
-// as units of their own on the 4-head instantiation: twice the workgroups, each half as long; the
-// cache is read twice, which such launches do not notice.  Measured (8 kv-heads, batch 1-32, contexts
-// 1k-32k): faster wherever there are up to 4 chunks per resident workgroup at 2 bits (30.5 -> 18.3 us
-// at batch 1 / context 4096, 69.6 -> 46.8 us at batch 2 / 32k; mixed beyond) and up to 16 at 4 bits,
-// whose 8-head instantiation spills registers (29.5 -> 18.9, 98.5 -> 81.9 us).
+// With 4, 6 or 8 query heads per kv-head and few chunks per workgroup the single launch lasts about
+// as long as its chunks, and a chunk takes longer the more heads it serves (8 kv-heads, context 4096,
+// batch 1, one chunk per workgroup: 9.8 / 15.2 / 30.0 us with 1 / 4 / 8 heads per kv-head).  Then the
+// two halves of every group run as units of their own on the instantiation for half as many heads:
+// twice the workgroups, each shorter; the cache is read twice, which such launches do not notice.
+// Measured (8 kv-heads, batch 1-32, contexts 1k-32k) for limits from 1/2 to 16 chunks per resident
+// workgroup.  6 or 8 heads: faster wherever applied up to 4 chunks per workgroup at 2 bits (30.5 ->
+// 18.3 us at batch 1 / context 4096, 69.6 -> 46.8 us at batch 2 / 32k; mixed beyond) and up to 16 at 4
+// bits, whose 8-head instantiation spills registers (29.5 -> 18.9, 98.5 -> 81.9 us).  4 heads at 2
+// bits: 17.0 -> 13.8 us at batch 1 / 4096, 37.1 -> 24.6 us at batch 1 / 32k; from 128 units on 4 % slower.
 bool wants_head_split(const kivi_layout_t* l, const SplitPlan& plan, int path, bool two_launches) {
     const int rep_total = l->n_q_heads / l->n_kv_heads;
-    if (path != KIVI_DECODE_MFMA || two_launches || (rep_total != 6 && rep_total != 8)) return false;
+    if (path != KIVI_DECODE_MFMA || two_launches || (rep_total != 4 && rep_total != 6 && rep_total != 8)) return false;
     const int64_t chunks = (int64_t)l->batch * l->n_kv_heads * plan.n_splits();
+    if (rep_total == 4) {
+        // 4 heads as 2 + 2 on the 2-head instantiation: 2 bits only (at 4 bits that instantiation's
+        // chunks are not the length the plan was made for), up to 64 units and 4 chunks per workgroup
+        const MfmaGeometry g2 = mfma_geometry(l->bits, 2);
+        return g2.chunk_tiles == plan.tiles_per_split_a && (int64_t)l->batch * l->n_kv_heads <= 64 &&
+               chunks <= (int64_t)g2.resident_workgroups * 4;
+    }
     const int max_chunks_per_workgroup = l->bits == 4 ? 16 : 4;
     return chunks <= (int64_t)mfma_geometry(l->bits, 4).resident_workgroups * max_chunks_per_workgroup;
 }
@@ -278,7 +287,7 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     p.rep_variant = std::min(rep_total, kMaxRep);
     if (wants_head_split(l, p.plan, path, two)) {
         p.head_split = 1;
-        p.rep_variant = 4;
+        p.rep_variant = rep_total == 4 ? 2 : 4;
         p.q_head0 = 0;
         p.rep_here = rep_total / 2;
         return hip_status(launch_decode_mfma(p, hs));

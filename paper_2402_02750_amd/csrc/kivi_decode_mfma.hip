@@ -1135,11 +1135,13 @@ bool with_variant(int bits, int rep_layout, F&& fn) {
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
     if (p.head_split > 0) {
-        // the two halves of every kv-head's query heads as units of their own, on the 4-head instantiation
-        if (p.two_launches > 0 || p.rep_variant != 4 || p.q_head0 != 0 || 2 * p.rep_here != p.n_q_heads / p.n_kv_heads)
+        // the two halves of every kv-head's query heads as units of their own, on the instantiation for half a group
+        if (p.two_launches > 0 || p.q_head0 != 0 || 2 * p.rep_here != p.n_q_heads / p.n_kv_heads || p.rep_variant < p.rep_here)
             return hipErrorInvalidValue;
-        if (p.bits == 2) return launch_one<2, 4, 4, 2, true>(p, stream);
-        if (p.bits == 4) return launch_one<4, 4, 2, 2, true>(p, stream);
+        if (p.bits == 2 && p.rep_variant == 4) return launch_one<2, 4, 4, 2, true>(p, stream);
+        if (p.bits == 4 && p.rep_variant == 4) return launch_one<4, 4, 2, 2, true>(p, stream);
+        if (p.bits == 2 && p.rep_variant == 2) return launch_one<2, 2, 4, 2, true>(p, stream);
+        if (p.bits == 4 && p.rep_variant == 2) return launch_one<4, 2, 4, 2, true>(p, stream);
         return hipErrorNotSupported;
     }
     with_variant(p.bits, p.rep_variant, [&](auto v) {

@@ -233,7 +233,10 @@ def test_decode_plan(lib):
     assert plan(1, 64, 8, 2, 3968, 128).units_per_kv_head == 2      # 8 units x 12 chunks
     assert plan(1, 48, 8, 4, 3968, 128).units_per_kv_head == 2
     assert plan(1, 56, 8, 2, 3968, 128).units_per_kv_head == 1      # 7 heads do not halve
-    assert plan(1, 32, 8, 2, 3968, 128).units_per_kv_head == 1      # 4 heads: nothing to split
+    assert plan(1, 32, 8, 2, 3968, 128).units_per_kv_head == 2      # 4 heads at 2 bits: 2 + 2
+    assert plan(1, 32, 8, 4, 3968, 128).units_per_kv_head == 1      # ... not at 4 bits
+    assert plan(16, 32, 8, 2, 992, 128).units_per_kv_head == 1      # ... not from 128 units on
+    assert plan(1, 16, 8, 2, 3968, 128).units_per_kv_head == 1      # 2 heads: nothing to split
     assert plan(16, 64, 8, 2, 16256, 128).units_per_kv_head == 1    # 128 units x 36 chunks: too many at 2 bits
     assert plan(32, 64, 8, 2, 3968, 128, path=kivi.KIVI_DECODE_MFMA_TWO).units_per_kv_head == 1
     assert plan(1, 64, 8, 2, 3968, 128, path=kivi.KIVI_DECODE_VALU).units_per_kv_head == 1
