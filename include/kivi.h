@@ -137,9 +137,9 @@ typedef struct kivi_decode_plan {
     int32_t splits_quantised;   /* pieces of the all-quantised token range per (batch, kv-head)     */
     int32_t splits_fp16;        /* pieces of the range that holds fp16 rows                         */
     int32_t tiles_per_split_quantised, tiles_per_split_fp16;   /* in 32-token tiles                */
-    int32_t units_per_kv_head;  /* 1; 2 when the query heads of every kv-head are served as two     */
-                                /* halves that read the cache independently (4, 6 or 8 heads per    */
-                                /* kv-head, small batches)                                           */
+    int32_t units_per_kv_head;  /* 1; 2 or 4 when the query heads of every kv-head are served as    */
+                                /* halves or quarters that read the cache independently (4, 6 or 8  */
+                                /* heads per kv-head, small batches)                                 */
 } kivi_decode_plan_t;
 
 /* Host helper: the plan for `cache`'s current state (no launch).  Errors: INVALID_ARG, UNSUPPORTED. */

@@ -51,10 +51,11 @@ int check_source(const void* x, int64_t sb, int64_t sh, int64_t st) {
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// The workspace starts with two finished-split counters per (batch, kv-head) -- one per half of the
-// kv-head's query heads, should a launch serve the halves as units of their own -- padded to 256 bytes.
+// The workspace starts with four finished-split counters per (batch, kv-head) -- one per quarter of
+// the kv-head's query heads, should a launch serve parts of the group as units of their own -- padded
+// to 256 bytes.
 size_t counter_bytes(const kivi_layout_t* l) {
-    return ((size_t)l->batch * l->n_kv_heads * 2 * sizeof(int32_t) + 255) / 256 * 256;
+    return ((size_t)l->batch * l->n_kv_heads * 4 * sizeof(int32_t) + 255) / 256 * 256;
 }
 
 // Upper bound of the number of context splits for any cache state of this layout.
@@ -221,27 +222,30 @@ bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path)
 
 // With 4, 6 or 8 query heads per kv-head and few chunks per workgroup the single launch lasts about
 // as long as its chunks, and a chunk takes longer the more heads it serves (8 kv-heads, context 4096,
-// batch 1, one chunk per workgroup: 9.8 / 15.2 / 30.0 us with 1 / 4 / 8 heads per kv-head).  Then the
-// two halves of every group run as units of their own on the instantiation for half as many heads:
-// twice the workgroups, each shorter; the cache is read twice, which such launches do not notice.
+// batch 1, one chunk per workgroup: 9.8 / 15.2 / 30.0 us with 1 / 4 / 8 heads per kv-head).  Then
+// equal parts of every group run as units of their own on the instantiation for a part's heads:
+// more workgroups, each shorter; the cache is read once per part, which such launches do not notice.
 // Measured (8 kv-heads, batch 1-32, contexts 1k-32k) for limits from 1/2 to 16 chunks per resident
-// workgroup.  6 or 8 heads: faster wherever applied up to 4 chunks per workgroup at 2 bits (30.5 ->
-// 18.3 us at batch 1 / context 4096, 69.6 -> 46.8 us at batch 2 / 32k; mixed beyond) and up to 16 at 4
-// bits, whose 8-head instantiation spills registers (29.5 -> 18.9, 98.5 -> 81.9 us).  4 heads at 2
-// bits: 17.0 -> 13.8 us at batch 1 / 4096, 37.1 -> 24.6 us at batch 1 / 32k; from 128 units on 4 % slower.
-bool wants_head_split(const kivi_layout_t* l, const SplitPlan& plan, int path, bool two_launches) {
+// workgroup.  Halves of 6 or 8 heads: faster wherever applied up to 4 chunks per workgroup at 2 bits
+// (30.5 -> 18.3 us at batch 1 / context 4096, 69.6 -> 46.8 us at batch 2 / 32k; mixed beyond) and up to
+// 16 at 4 bits, whose 8-head instantiation spills registers (29.5 -> 18.9, 98.5 -> 81.9 us).  Halves of
+// 4 heads at 2 bits: 17.0 -> 13.8 us at batch 1 / 4096, 37.1 -> 24.6 us at batch 1 / 32k; from 128 units
+// on 4 % slower.  Quarters of 8 heads at 2 bits, against halves: 18.3 -> 14.5 us at batch 1 / 4096,
+// 29.7 -> 22.4 us at batch 1 / 16k, 20.4 -> 18.0 us at batch 2 / 4096; even or slower from 32 units on.
+// log2 of the parts a kv-head's query heads are served in: 0 (whole group), 1 (halves), 2 (quarters)
+int head_split_shift(const kivi_layout_t* l, const SplitPlan& plan, int path, bool two_launches) {
     const int rep_total = l->n_q_heads / l->n_kv_heads;
-    if (path != KIVI_DECODE_MFMA || two_launches || (rep_total != 4 && rep_total != 6 && rep_total != 8)) return false;
-    const int64_t chunks = (int64_t)l->batch * l->n_kv_heads * plan.n_splits();
-    if (rep_total == 4) {
-        // 4 heads as 2 + 2 on the 2-head instantiation: 2 bits only (at 4 bits that instantiation's
-        // chunks are not the length the plan was made for), up to 64 units and 4 chunks per workgroup
-        const MfmaGeometry g2 = mfma_geometry(l->bits, 2);
-        return g2.chunk_tiles == plan.tiles_per_split_a && (int64_t)l->batch * l->n_kv_heads <= 64 &&
-               chunks <= (int64_t)g2.resident_workgroups * 4;
-    }
+    if (path != KIVI_DECODE_MFMA || two_launches || (rep_total != 4 && rep_total != 6 && rep_total != 8)) return 0;
+    const int64_t units = (int64_t)l->batch * l->n_kv_heads, chunks = units * plan.n_splits();
+    // parts of 2 heads run on the 2-head instantiation: 2 bits only (at 4 bits that instantiation's
+    // chunks are not the length the plan was made for)
+    const MfmaGeometry g2 = mfma_geometry(l->bits, 2);
+    const bool two_heads_possible = g2.chunk_tiles == plan.tiles_per_split_a;
+    if (rep_total == 8 && two_heads_possible && units <= 16 && chunks <= (int64_t)g2.resident_workgroups * 2) return 2;     // quarters
+    if (rep_total == 4)     // 2 + 2: up to 64 units and 4 chunks per workgroup
+        return two_heads_possible && units <= 64 && chunks <= (int64_t)g2.resident_workgroups * 4 ? 1 : 0;
     const int max_chunks_per_workgroup = l->bits == 4 ? 16 : 4;
-    return chunks <= (int64_t)mfma_geometry(l->bits, 4).resident_workgroups * max_chunks_per_workgroup;
+    return chunks <= (int64_t)mfma_geometry(l->bits, 4).resident_workgroups * max_chunks_per_workgroup ? 1 : 0;
 }
 
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the
@@ -285,11 +289,11 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     // matrix-core kernel leaves its counters at zero).  Only the first one appends the new token.
     const int rep_total = l->n_q_heads / l->n_kv_heads;
     p.rep_variant = std::min(rep_total, kMaxRep);
-    if (wants_head_split(l, p.plan, path, two)) {
-        p.head_split = 1;
-        p.rep_variant = rep_total == 4 ? 2 : 4;
+    if (const int shift = head_split_shift(l, p.plan, path, two)) {
+        p.head_split = shift;
         p.q_head0 = 0;
-        p.rep_here = rep_total / 2;
+        p.rep_here = rep_total >> shift;
+        p.rep_variant = p.rep_here <= 2 ? 2 : 4;
         return hip_status(launch_decode_mfma(p, hs));
     }
     for (int h0 = 0; h0 < rep_total; h0 += kMaxRep) {
@@ -371,7 +375,7 @@ int kivi_decode_plan(const kivi_layout_t* l, const kivi_cache_t* c, kivi_decode_
     const SplitPlan plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
     out->family = path;
     out->launches = path == KIVI_DECODE_MFMA ? (two ? 2 : 1) : 2;       // vector-ALU family: decode + merge
-    out->units_per_kv_head = wants_head_split(l, plan, path, two) ? 2 : 1;
+    out->units_per_kv_head = 1 << head_split_shift(l, plan, path, two);
     out->splits_quantised = plan.n_splits_a;
     out->splits_fp16 = plan.n_splits_b;
     out->tiles_per_split_quantised = plan.tiles_per_split_a;

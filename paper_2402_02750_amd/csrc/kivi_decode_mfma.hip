@@ -276,7 +276,7 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
 // first launch into it.
 constexpr int kBothPhases = 0, kQuantisedOnly = 1;
 
-template <int BITS, int REP, int SLOTS, int OCC, int MODE, bool HSPLIT = false>
+template <int BITS, int REP, int SLOTS, int OCC, int MODE, int HSHIFT = 0>
 __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     constexpr int kSlots = SLOTS;
     // tile slots staged at once: two where that divides the slots and the registers allow
@@ -314,12 +314,13 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
     // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
     const int rep = p.rep_here, rep_total = p.n_q_heads / p.n_kv_heads;
-    // HSPLIT: a unit of the work axis is (batch, kv-head, half of the kv-head's query heads) -- unit u
-    // reads the cache of (batch, kv-head) u / 2 and serves the query heads (u & 1) * rep .. + rep of
-    // its group; parts, counters and held results go by u.
-    auto kv_unit = [&](int u) -> int { return HSPLIT ? u >> 1 : u; };
+    // HSHIFT > 0: a unit of the work axis is (batch, kv-head, one of 2^HSHIFT equal parts of the
+    // kv-head's query heads) -- unit u reads the cache of (batch, kv-head) u >> HSHIFT and serves the
+    // query heads (u & (2^HSHIFT - 1)) * rep .. + rep of its group; parts, counters and held results go by u.
+    constexpr int kPartMask = (1 << HSHIFT) - 1;
+    auto kv_unit = [&](int u) -> int { return u >> HSHIFT; };
     auto first_q_head = [&](int u) -> int {
-        return (kv_unit(u) % p.n_kv_heads) * rep_total + p.q_head0 + (HSPLIT ? (u & 1) * rep : 0);
+        return (kv_unit(u) % p.n_kv_heads) * rep_total + p.q_head0 + (u & kPartMask) * rep;
     };
     auto batch_of = [&](int u) -> int { return kv_unit(u) / p.n_kv_heads; };
     // chunks per unit on this launch's cost axis: all-quantised / with fp16 rows
@@ -815,7 +816,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             if (fused_append) {
                 const int last = p.length - 1, last_tile = last / kTileTokens;
                 owns_new = last_tile >= tile0 && last_tile < tile0 + n_tiles && ((last_tile - tile0) & 3) == wave && lane < 32 &&
-                           (!HSPLIT || (u & 1) == 0);      // the two halves of a kv-head would store the same rows
+                           (u & kPartMask) == 0;      // the parts of a kv-head's group would all store the same rows
                 if (owns_new) {
                     const bool is_v = lane >= 16;
                     const int slot = is_v ? ring_slot(p.v_r_start, last - p.n_vq, p.cap_r)
@@ -1047,14 +1048,14 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 }
 
 // Workgroups the chip holds at once for one instantiation (occupancy query, cached).
-template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases, bool HSPLIT = false>
+template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases, int HSHIFT = 0>
 int resident_workgroups() {
     static int cached = 0;
     if (cached == 0) {
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE, HSPLIT>, 256, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE, HSHIFT>, 256, 0) != hipSuccess ||
             cus <= 0 || per_cu <= 0)
             return 256 * OCC;
         cached = cus * per_cu;
@@ -1062,10 +1063,10 @@ int resident_workgroups() {
     return cached;
 }
 
-template <int BITS, int REP, int SLOTS, int OCC, bool HSPLIT = false>
+template <int BITS, int REP, int SLOTS, int OCC, int HSHIFT = 0>
 hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
-    const int64_t units = (int64_t)p.batch * p.n_kv_heads * (HSPLIT ? 2 : 1);
+    const int64_t units = ((int64_t)p.batch * p.n_kv_heads) << HSHIFT;
     const int64_t total_a = units * p.plan.n_splits_a, total_b = units * p.plan.n_splits_b;
     // Cost of an fp16-row chunk in units of an all-quantised chunk: by the bytes they stream, times
     // a measured factor per instantiation -- with 5 to 8 query heads per kv-head, and with 3 or 4 at
@@ -1084,9 +1085,9 @@ hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     p.total_chunks_a = (int)total_a;
     p.total_chunks_b = (int)total_b;
     // every resident workgroup gets an equal share of the cost axis (within one unit of cost)
-    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kBothPhases, HSPLIT>(),
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kBothPhases, HSHIFT>(),
                                                                   p.total_cost / p.cost_b));
-    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kBothPhases, HSPLIT><<<grid, 256, 0, stream>>>(p);
+    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kBothPhases, HSHIFT><<<grid, 256, 0, stream>>>(p);
     return hipGetLastError();
 }
 
@@ -1135,13 +1136,15 @@ bool with_variant(int bits, int rep_layout, F&& fn) {
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
     if (p.head_split > 0) {
-        // the two halves of every kv-head's query heads as units of their own, on the instantiation for half a group
-        if (p.two_launches > 0 || p.q_head0 != 0 || 2 * p.rep_here != p.n_q_heads / p.n_kv_heads || p.rep_variant < p.rep_here)
+        // 2^head_split equal parts of every kv-head's query heads as units of their own, on the
+        // instantiation for one part
+        if (p.two_launches > 0 || p.q_head0 != 0 || (p.rep_here << p.head_split) != p.n_q_heads / p.n_kv_heads ||
+            p.rep_variant < p.rep_here)
             return hipErrorInvalidValue;
-        if (p.bits == 2 && p.rep_variant == 4) return launch_one<2, 4, 4, 2, true>(p, stream);
-        if (p.bits == 4 && p.rep_variant == 4) return launch_one<4, 4, 2, 2, true>(p, stream);
-        if (p.bits == 2 && p.rep_variant == 2) return launch_one<2, 2, 4, 2, true>(p, stream);
-        if (p.bits == 4 && p.rep_variant == 2) return launch_one<4, 2, 4, 2, true>(p, stream);
+        if (p.head_split == 1 && p.bits == 2 && p.rep_variant == 4) return launch_one<2, 4, 4, 2, 1>(p, stream);
+        if (p.head_split == 1 && p.bits == 4 && p.rep_variant == 4) return launch_one<4, 4, 2, 2, 1>(p, stream);
+        if (p.head_split == 1 && p.bits == 2 && p.rep_variant == 2) return launch_one<2, 2, 4, 2, 1>(p, stream);
+        if (p.head_split == 2 && p.bits == 2 && p.rep_variant == 2) return launch_one<2, 2, 4, 2, 2>(p, stream);
         return hipErrorNotSupported;
     }
     with_variant(p.bits, p.rep_variant, [&](auto v) {

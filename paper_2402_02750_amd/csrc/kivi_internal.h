@@ -106,9 +106,9 @@ struct DecodeParams {
     // > 0: the matrix-core family runs as two launches (fp16 rows, then the all-quantised chunks); the
     // plan then has a single fp16-row split per unit (n_splits_b == 1).
     int32_t two_launches;
-    // > 0 (single launch, 4, 6 or 8 query heads per kv-head, small batches): every kv-head's query
-    // heads are served as two halves, each a unit of its own on the instantiation for half a group
-    // (rep_variant 2 or 4, rep_here = half the group); the cache is read once per half.
+    // k > 0 (single launch, 4, 6 or 8 query heads per kv-head, small batches): every kv-head's query
+    // heads are served as 2^k equal parts, each a unit of its own on the instantiation for one part
+    // (rep_variant 2 or 4, rep_here = heads of a part); the cache is read once per part.
     int32_t head_split;
 };
 

@@ -230,7 +230,9 @@ def test_decode_plan(lib):
     assert plan(64, 32, 32, 2, 1920, 150, path=kivi.KIVI_DECODE_MFMA_ONE).launches == 1
     assert plan(16, 32, 32, 2, 3968, 128, path=kivi.KIVI_DECODE_MFMA_TWO).launches == 2
     # 6 or 8 query heads per kv-head and few chunks per workgroup: the halves of every group as units of their own
-    assert plan(1, 64, 8, 2, 3968, 128).units_per_kv_head == 2      # 8 units x 12 chunks
+    assert plan(1, 64, 8, 2, 3968, 128).units_per_kv_head == 4      # 8 units x 12 chunks, 2 bits: quarters
+    assert plan(4, 64, 8, 2, 3968, 128).units_per_kv_head == 2      # 32 units: halves
+    assert plan(1, 64, 8, 4, 3968, 128).units_per_kv_head == 2      # 4 bits: halves
     assert plan(1, 48, 8, 4, 3968, 128).units_per_kv_head == 2
     assert plan(1, 56, 8, 2, 3968, 128).units_per_kv_head == 1      # 7 heads do not halve
     assert plan(1, 32, 8, 2, 3968, 128).units_per_kv_head == 2      # 4 heads at 2 bits: 2 + 2

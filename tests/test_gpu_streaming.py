@@ -51,7 +51,7 @@ def test_streaming_small(path, policy, bits):
 @pytest.mark.parametrize("path", [kivi.KIVI_DECODE_VALU, kivi.KIVI_DECODE_MFMA, kivi.KIVI_DECODE_MFMA_TWO], ids=["valu", "mfma", "mfma2"])
 @pytest.mark.parametrize("policy", [kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_FLUSH_ALG1], ids=["window", "alg1"])
 @pytest.mark.parametrize("bits,rep,group", [(2, 1, 32), (4, 2, 32), (2, 4, 32), (2, 1, 64), (4, 1, 128), (2, 12, 32),
-                                            (4, 4, 32), (4, 8, 64)])
+                                            (4, 4, 32), (4, 8, 64), (2, 8, 32)])
 def test_decode_step_matches_oracle(path, policy, bits, rep, group):
     """kivi_decode_step (append + flush + attention, one launch on the steps without a flush in the
     matrix-core family): the residual rings must hold the new token afterwards (bit-exact cache
