@@ -25,17 +25,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
-# HBM bytes per decode-attention launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by the factor a plain copy kernel of known size reads on the same counters; see the
-# summaries under profiles/.  None until measured for a workload/path.
-MEASURED_TRAFFIC = {
-    # profiles/decode_mfma_llama7b.md: FETCH_SIZE 111996.2 KiB x 2.0 + WRITE_SIZE 387.1 KiB x 1.0
-    ("llama7b", "mfma"): 111996.2 * 1024 * 2.0 + 387.1 * 1024,
-    ("llama7b", "auto"): 111996.2 * 1024 * 2.0 + 387.1 * 1024,
-    # profiles/decode_mfma_other_workloads.md, stream: mean per step of the two attention kernels
-    # (73891.9 + 196238.2) KiB x 2.0 read, (2080.0 + 1024.0) KiB written
-    ("stream", "auto"): (73891.9 + 196238.2) * 1024 * 2.0 + (2080.0 + 1024.0) * 1024,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(workload: str, path: str):
+    """HBM bytes per decode-attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+    what a plain copy of known size reads on the same counters.  The figures are not measured here:
+    they are read from profiles/hbm_traffic.txt, which is rewritten whenever the counters are
+    collected again for a changed kernel (lines `<workload> <path> <bytes> <kernel revision>`).
+    None when the file has no line for this workload and path."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and not line.startswith("#") and parts[0] == workload and parts[1] == path:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
 
 
 def parse_args():
@@ -43,7 +50,12 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=500,
-                    help="untimed steps; a few hundred let the clocks settle (a step is ~50 us)")
+                    help="untimed steps run before the timed ones, after the clocks have settled")
+    ap.add_argument("--roofline-launches", type=int, default=2000,
+                    help="launches of the attention-only loop the roofline figure is timed over (its own count, "
+                         "independent of --steps)")
+    ap.add_argument("--settle-seconds", type=float, default=0.3,
+                    help="least duration of the untimed phase that lets the clocks settle")
     ap.add_argument("--workload", default="llama7b", choices=["tiny", "llama7b", "stream", "llama13b_4bit", "mistral_gqa"])
     ap.add_argument("--path", default="auto", choices=["auto", "valu", "mfma", "mfma1", "mfma2"])
     ap.add_argument("--copies", type=int, default=5)
@@ -60,36 +72,52 @@ def parse_args():
 
 
 def cpu_baseline(w, k, v, q, seconds):
-    """Time the oracle's decode attention (as it stands) on a bounded sample of kv-heads."""
+    """Time the oracle's decode attention (as it stands) on a bounded sample of kv-heads: half of
+    the time budget with the numerical library's thread pool as it comes (all host cores it
+    uses), half limited to one thread."""
     import numpy as np
     from oracle import kivi_oracle as ko
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
+        threadpool_limits = None
         threads = 1
     n_q, n_r = w.split_single_step()
     rep = w.q_per_kv
     heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
-    # Units are walked in order, pass after pass over the batch, until `seconds` of oracle time are
-    # spent (one pass of a small workload takes about a second: too short a sample on a busy host).
-    done, t_total = 0, 0.0
-    while t_total < seconds:
-        for (b, h) in heads:
-            kk, vv = k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1]
-            kq = ko.quantize_key(kk[:, :, :n_q], w.bits, w.group)       # setup, not timed
-            vq = ko.quantize_value(vv[:, :, :n_q], w.bits, w.group)
-            qq = q[b:b + 1, h * rep:(h + 1) * rep]
-            t0 = time.perf_counter()
-            ko.decode_attention(qq, kq, kk[:, :, n_q:], vq, vv[:, :, n_q:], w.group, w.softmax_scale)
-            t_total += time.perf_counter() - t0
-            done += 1
-            if t_total >= seconds:
-                break
+
+    def sample(budget):
+        # Units are walked in order, pass after pass over the batch, until `budget` seconds of oracle
+        # time are spent (one pass of a small workload takes about a second: too short a sample on
+        # a busy host).
+        done, t_total = 0, 0.0
+        while t_total < budget:
+            for (b, h) in heads:
+                kk, vv = k[b:b + 1, h:h + 1], v[b:b + 1, h:h + 1]
+                kq = ko.quantize_key(kk[:, :, :n_q], w.bits, w.group)       # setup, not timed
+                vq = ko.quantize_value(vv[:, :, :n_q], w.bits, w.group)
+                qq = q[b:b + 1, h * rep:(h + 1) * rep]
+                t0 = time.perf_counter()
+                ko.decode_attention(qq, kq, kk[:, :, n_q:], vq, vv[:, :, n_q:], w.group, w.softmax_scale)
+                t_total += time.perf_counter() - t0
+                done += 1
+                if t_total >= budget:
+                    break
+        return done, t_total
+
+    done, t_total = sample(seconds / 2)
     per_step = t_total / done * len(heads)
-    return {"value": w.batch / per_step, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"decode attention of {done} (batch, kv-head) units ({done / len(heads):.1f} passes over the "
-                      f"{len(heads)} units of the same workload), {t_total:.1f} s of oracle time, scaled to one pass"}
+    result = {"value": w.batch / per_step, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+              "sample": f"decode attention of {done} (batch, kv-head) units ({done / len(heads):.1f} passes over the "
+                        f"{len(heads)} units of the same workload), {t_total:.1f} s of oracle time, scaled to one pass; "
+                        f"`cores` = threads of the numerical library's pool"}
+    if threadpool_limits is not None and threads > 1:
+        with threadpool_limits(limits=1):
+            done1, t1 = sample(seconds / 2)
+        result["single_thread"] = {"value": w.batch / (t1 / done1 * len(heads)), "unit": "tokens/s", "cores": 1,
+                                   "sample": f"{done1} units, {t1:.1f} s, pool limited to one thread"}
+    return result
 
 
 def run_stream(args, w, path_name, path):
@@ -116,23 +144,40 @@ def run_stream(args, w, path_name, path):
     stream = torch.cuda.current_stream()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
-    def one_pass():
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(w.decode_steps + 1)]
+
+    def one_pass(mark_steps=False):
         cache.c.n_kq = cache.c.n_vq = cache.c.n_kr = cache.c.n_vr = 0
         kivi.kivi_prefill(layout, kt, vt, w.prompt, cache)
-        bytes_total, flushes = 0, 0
-        ev0.record(stream)
+        bytes_total, flush_steps = 0, []
+        marks[0].record(stream)
         for s in range(w.decode_steps):
             before = cache.c.n_kq
             kivi.kivi_decode_step(layout, cache, k_new[s], v_new[s], qs[s], w.softmax_scale, out,
                                   kivi.KIVI_FLUSH_WINDOW, stream)
-            flushes += cache.c.n_kq != before
+            if mark_steps or s == w.decode_steps - 1:
+                marks[s + 1].record(stream)
+            if cache.c.n_kq != before:
+                flush_steps.append(s)
             bytes_total += w.algorithmic_bytes(cache.c.n_kq, cache.c.n_kr)["all"]
-        ev1.record(stream)
         torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1), bytes_total, flushes
+        per_step = [marks[s].elapsed_time(marks[s + 1]) for s in range(w.decode_steps)] if mark_steps else None
+        return marks[0].elapsed_time(marks[w.decode_steps]), bytes_total, flush_steps, per_step
 
-    one_pass()
-    ms, bytes_total, flushes = one_pass()
+    # untimed passes until the clocks have settled (two consecutive passes within 1 %, at least
+    # --settle-seconds, at most 3 s), then the timed pass
+    t_settle, prev_ms = time.perf_counter(), None
+    while True:
+        ms = one_pass()[0]
+        elapsed = time.perf_counter() - t_settle
+        if (prev_ms is not None and abs(ms - prev_ms) <= 0.01 * prev_ms and elapsed >= args.settle_seconds) or elapsed > 3.0:
+            break
+        prev_ms = ms
+    ms, bytes_total, flush_steps, _ = one_pass()                 # the timed pass: events at its two ends only
+    per_step = one_pass(mark_steps=True)[3]                      # once more with an event after every step
+    flushes = len(flush_steps)
+    flush_ms = [per_step[s] for s in flush_steps]
+    plain_ms = [per_step[s] for s in range(w.decode_steps) if s not in set(flush_steps)]
     achieved = bytes_total / (ms * 1e-3) / 1e9
     return {
         "metric": "decode-attn tokens/s over 2-bit KV; achieved HBM GB/s vs MI355X peak",
@@ -150,10 +195,15 @@ def run_stream(args, w, path_name, path):
                    "attention_launches": kivi.kivi_decode_plan(layout, cache).launches,
                    "step": "kivi_decode_step: append newest token + flush (every 32nd step) + decode attention"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get((w.name, path_name)),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, path_name),
                      "kernel": "whole steps (attention kernel plus, on flush steps, the copy and quantise kernels): "
                                "sum of the attention's algorithmic bytes over the steps / time of all steps",
                      "algorithmic_bytes_per_launch": bytes_total / w.decode_steps},
+        "extra": {"flush_steps": flushes,
+                  "ms_per_flush_step": sum(flush_ms) / max(len(flush_ms), 1),
+                  "ms_per_step_without_flush": sum(plain_ms) / max(len(plain_ms), 1),
+                  "note": "per-step times between HIP events recorded after every step of the timed pass; a flush "
+                          "step appends, quantises one group of keys and values out of the rings and runs the attention"},
     }
 
 
@@ -218,7 +268,9 @@ def main():
         kivi.kivi_decode_step(layout, c, k_new, v_new, qt, w.softmax_scale, out, kivi.KIVI_FLUSH_WINDOW, stream)
 
     def timed(n_steps, rotate, attention_only):
-        """Average GPU time per iteration between two events on the launch stream."""
+        """Average GPU time per iteration between two events on the launch stream; also the host's
+        time per iteration to enqueue them (if that came close to the GPU time the launches would
+        not be back to back)."""
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record(stream)
@@ -229,19 +281,40 @@ def main():
             else:
                 step(c)
         ev1.record(stream)
+        enqueue_ms = (time.perf_counter() - t0) * 1e3
         torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3
-        return ev0.elapsed_time(ev1) / n_steps, wall_ms / n_steps
+        return ev0.elapsed_time(ev1) / n_steps, enqueue_ms / n_steps
 
-    for i in range(args.warmup):
-        step(caches[i % len(caches)])
-    torch.cuda.synchronize()
-    cold_step_ms, cold_wall_ms = timed(args.steps, rotate=True, attention_only=False)
-    warm_step_ms, _ = timed(args.steps, rotate=False, attention_only=False)
-    # the dominant kernel alone: back-to-back decode-attention launches (one kernel per launch in the
-    # matrix-core family), cold = rotating over the cache copies
-    cold_attn_ms, _ = timed(args.steps, rotate=True, attention_only=True)
-    warm_attn_ms, _ = timed(args.steps, rotate=False, attention_only=True)
+    # Clocks first, independently of --warmup: untimed blocks of 200 steps until two consecutive
+    # blocks agree within 1 % and --settle-seconds have passed (at most 3 s).
+    t_settle, prev_ms, settle_blocks = time.perf_counter(), None, 0
+    while True:
+        ms, _ = timed(200, rotate=True, attention_only=False)
+        settle_blocks += 1
+        elapsed = time.perf_counter() - t_settle
+        if (prev_ms is not None and abs(ms - prev_ms) <= 0.01 * prev_ms and elapsed >= args.settle_seconds) or elapsed > 3.0:
+            break
+        prev_ms = ms
+
+    def measure():
+        for i in range(args.warmup):
+            step(caches[i % len(caches)])
+        cold_step_ms, enqueue_ms = timed(args.steps, rotate=True, attention_only=False)      # EXACTLY --steps steps
+        warm_step_ms, _ = timed(max(args.steps, 200), rotate=False, attention_only=False)
+        # the dominant kernel alone: back-to-back decode-attention launches (one kernel per launch in the
+        # single-launch form), cold = rotating over the cache copies; its own launch count
+        cold_attn_ms, _ = timed(args.roofline_launches, rotate=True, attention_only=True)
+        warm_attn_ms, _ = timed(args.roofline_launches, rotate=False, attention_only=True)
+        return cold_step_ms, enqueue_ms, warm_step_ms, cold_attn_ms, warm_attn_ms
+
+    cold_step_ms, enqueue_ms, warm_step_ms, cold_attn_ms, warm_attn_ms = measure()
+    # A step contains the attention launch: the launch alone cannot take longer than the step.  If the
+    # two loops disagree by more than 2 % (clocks moved between them), measure once more.
+    remeasured = False
+    if cold_attn_ms > cold_step_ms * 1.02:
+        remeasured = True
+        cold_step_ms, enqueue_ms, warm_step_ms, cold_attn_ms, warm_attn_ms = measure()
+    consistent = cold_attn_ms <= cold_step_ms * 1.02
 
     # Yardstick: the library's plain read-only stream kernel on this machine -- over as many bytes as
     # one attention launch moves (rotating over different buffers, so cold like the launches above)
@@ -290,12 +363,14 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC.get((w.name, args.path)),
+            "traffic": measured_traffic(w.name, args.path),
             "kernel": "kivi_decode_attention: back-to-back launches between two HIP events on the launch stream, rotating cache copies (cold)",
             "algorithmic_bytes_per_launch": bytes_["all"],
             "achieved_packed_only": achieved_packed,
             "frac_packed_only": achieved_packed / HBM_PEAK_GBS,
             "launch_us": cold_attn_ms * 1e3,
+            "launches_timed": args.roofline_launches,
+            "consistent_with_ms_per_step": consistent,
             "stream_read_GBs_same_bytes": stream_same_size,
             "stream_read_GBs_1GiB": stream_1gib,
             "frac_of_stream_same_bytes": achieved / stream_same_size,
@@ -303,7 +378,8 @@ def main():
         "extra": {
             "warm_ms_per_step": warm_step_ms, "warm_attn_us": warm_attn_ms * 1e3,
             "warm_achieved_GBs": bytes_["all"] / (warm_attn_ms * 1e-3) / 1e9,
-            "host_wall_ms_per_step": cold_wall_ms,
+            "host_enqueue_ms_per_step": enqueue_ms,
+            "settle_blocks_of_200_steps": settle_blocks, "remeasured": remeasured,
             "prefill_quantize_ms": prefill_ms,
             "prefill_GBs": (2 * k.nbytes + bytes_["packed"] + bytes_["residual"]) / (prefill_ms * 1e-3) / 1e9,
         },

@@ -36,12 +36,7 @@
 #include <hip/hip_fp16.h>
 
 #include <algorithm>
-
-#ifndef KIVI_V21_SLOTS
-#define KIVI_V21_SLOTS 4
-#define KIVI_V21_OCC 2
-#endif
-
+#include <atomic>
 
 namespace kivi {
 namespace {
@@ -615,8 +610,13 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             }
         }
         if (n_parts > 1) {
-            // the last workgroup to finish this unit merges the parts
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");     // the stores above are acknowledged
+            // The last workgroup to finish this unit merges the parts.  Publication follows the memory
+            // model: every thread orders its own part stores before the barrier with a release fence
+            // at device scope (it waits until they have been acknowledged by memory), the counter
+            // increment after the barrier then tells the other workgroups that all of them are
+            // visible, and whoever sees the final count takes an acquire fence at device scope before
+            // it reads the parts of the others.
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
             __syncthreads();
             if (tid == 0) {
                 const int done = __hip_atomic_fetch_add(p.counters + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -624,6 +624,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             }
             __syncthreads();
             if (sm_last) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                 for (int idx = tid; idx < rep * kHeadDim; idx += 256) {
                     const int hh = idx / kHeadDim, c = idx % kHeadDim;
                     const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
@@ -1047,20 +1048,26 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     }
 }
 
-// Workgroups the chip holds at once for one instantiation (occupancy query, cached).
+// Workgroups the current device holds at once for one instantiation: an occupancy query, whose
+// answer is kept per device (the only state the library keeps; a plain integer per device and
+// instantiation, written once with the same value by whichever thread asks first).
+constexpr int kMaxDevices = 64;
 template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases, int HSHIFT = 0>
 int resident_workgroups() {
-    static int cached = 0;
-    if (cached == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE, HSHIFT>, 256, 0) != hipSuccess ||
-            cus <= 0 || per_cu <= 0)
-            return 256 * OCC;
-        cached = cus * per_cu;
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256 * OCC;
+    const bool keep = dev >= 0 && dev < kMaxDevices;
+    if (keep) {
+        const int c = cached[dev].load(std::memory_order_relaxed);
+        if (c > 0) return c;
     }
-    return cached;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE, HSHIFT>, 256, 0) != hipSuccess ||
+        cus <= 0 || per_cu <= 0)
+        return 256 * OCC;
+    if (keep) cached[dev].store(cus * per_cu, std::memory_order_relaxed);
+    return cus * per_cu;
 }
 
 template <int BITS, int REP, int SLOTS, int OCC, int HSHIFT = 0>
@@ -1120,7 +1127,7 @@ template <class F>
 bool with_variant(int bits, int rep_layout, F&& fn) {
     // the smallest instantiation that holds the layout's query heads per kv-head
     const int rep = rep_layout <= 2 ? rep_layout : (rep_layout <= 4 ? 4 : (rep_layout <= 8 ? 8 : 0));
-    if (bits == 2 && rep == 1) { fn(Variant<2, 1, KIVI_V21_SLOTS, KIVI_V21_OCC>{}); return true; }
+    if (bits == 2 && rep == 1) { fn(Variant<2, 1, 4, 2>{}); return true; }
     if (bits == 2 && rep == 2) { fn(Variant<2, 2, 4, 2>{}); return true; }
     if (bits == 2 && rep == 4) { fn(Variant<2, 4, 4, 2>{}); return true; }
     if (bits == 4 && rep == 1) { fn(Variant<4, 1, 4, 2>{}); return true; }

@@ -11,7 +11,7 @@
 namespace kivi {
 
 constexpr int kHeadDim = 128;
-constexpr int kTileTokens = 32;        // tokens per code tile == supported group size G
+constexpr int kTileTokens = 32;        // tokens per code tile; a group of G = 32, 64 or 128 tokens covers 1, 2 or 4 tiles
 constexpr int kMaxSplitTiles = 32;     // a context split covers at most 32 tiles (1024 tokens)
 constexpr int kMfmaSplitTiles = 16;    // ... at most 16 tiles in the matrix-core family (4 per wavefront)
 constexpr int kMaxRep = 8;             // query heads per kv-head handled by one launch

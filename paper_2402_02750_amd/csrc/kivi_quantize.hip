@@ -2,9 +2,12 @@
 //
 // One workgroup stages one 32-token x 128-channel fp16 tile in LDS (coalesced 16-byte loads),
 // derives the per-group zero-point/scale, then every thread assembles whole 32-bit words of the
-// packed tile, so all global stores are full, coalesced dwords.  The arithmetic of a code is
-// bit-contract: fp32 subtract, IEEE fp32 division, round-half-even, clamp.  This file is
-// compiled with -ffp-contract=off so no FMA can slip into it.
+// packed tile, so all global stores are full, coalesced dwords.  The value of a code is
+// bit-contract: fp32 subtract, IEEE fp32 division, round-half-even, clamp (encode()).  The fast
+// path reaches the same code with one explicit fused multiply-add per element (encode_fast()) and
+// falls back to encode() for a word whenever a quotient lies close enough to a rounding tie for
+// the two to differ.  This file is compiled with -ffp-contract=off, so the only fused operations
+// are the ones written as fmaf().
 #include "kivi_internal.h"
 
 #include <hip/hip_fp16.h>
