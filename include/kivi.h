@@ -13,8 +13,10 @@
  *     launched and no cache field is changed;
  *   - work is enqueued on the caller's HIP stream (`stream` is a hipStream_t passed as void*;
  *     NULL = the default stream) and the call returns without synchronising;
- *   - the library never allocates or frees memory and keeps no global state: all buffers,
- *     including the attention workspace, belong to the caller;
+ *   - the library never allocates or frees memory: all buffers, including the attention
+ *     workspace, belong to the caller (kivi_decode_attention_static is the one exception: its
+ *     workspace is an array inside the library).  The only state it keeps between calls is, per
+ *     device, the answer of one occupancy query per kernel instantiation, and that array's address;
  *   - pointers inside kivi_cache_t, `q`, `out`, `workspace` and the fp16 source tensors are DEVICE
  *     pointers, 16-byte aligned; the structs themselves and all counts live on the host;
  *   - the kernels work on batches of equal length; kivi_decode_step_ragged / kivi_decode_attention_ragged
@@ -194,8 +196,9 @@ int kivi_append_residual(const kivi_layout_t* layout, kivi_cache_t* cache, const
                          const void* v_new, void* stream);
 
 /*
- * Move the oldest residual tokens into the quantised part -- Section 3.3 ("once X_Kr reaches R
- * tokens ... we quantize and concatenate it"; the value queue) and Algorithm 1 (Decoding).
+ * Move the oldest residual tokens into the quantised part -- Section 3.3 (the key residual is
+ * quantised as a whole when it is full; the value residual is a queue of R tokens) and
+ * Algorithm 1 (Decoding).
  * `policy` is KIVI_FLUSH_WINDOW or KIVI_FLUSH_ALG1 (see above).  A call that finds nothing to
  * flush enqueues nothing.  On return the cache counters describe the new split.
  * Optional outputs (host, may be NULL): number of key / value tokens quantised by this call.
@@ -222,6 +225,29 @@ int kivi_flush_residual(const kivi_layout_t* layout, kivi_cache_t* cache, int32_
 int kivi_decode_attention(const kivi_layout_t* layout, const kivi_cache_t* cache, const void* q,
                           float softmax_scale, float* out, void* workspace, size_t workspace_bytes,
                           void* stream);
+
+/*
+ * kivi_decode_attention for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and result as kivi_decode_attention, but the partial results of the context splits and
+ * their counters live in a static device array of KIVI_STATIC_WORKSPACE_BYTES inside the library
+ * (one copy per GPU, held until the process ends).  The call allocates and frees nothing.
+ *   - A cache state whose counters and parts need more than the array holds is refused with
+ *     KIVI_ERR_WORKSPACE and nothing is launched.  The need of a state is
+ *     round_up(16 * batch * n_kv_heads, 256) + 520 * batch * n_q_heads * (splits_quantised + splits_fp16)
+ *     bytes with the splits kivi_decode_plan reports (configurations of up to 2048 query-head rows
+ *     with a 4096-token context, or 128 rows with 32768 tokens, need 2.5 to 6.5 MB).
+ *   - All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two
+ *     threads) race.  Calls on one stream, or otherwise ordered, are fine; the array's contents from
+ *     one call are not needed by the next (the counters at its start are cleared by a small fill
+ *     kernel at the start of every call).
+ *   - The first call on a device resolves the array's address there (hipGetSymbolAddress); make that
+ *     call outside a graph capture.
+ * Errors: as kivi_decode_attention; KIVI_ERR_UNSUPPORTED for a device ordinal of 64 or more.
+ */
+#define KIVI_STATIC_WORKSPACE_BYTES (8u << 20)
+int kivi_decode_attention_static(const kivi_layout_t* layout, const kivi_cache_t* cache, const void* q,
+                                 float softmax_scale, float* out, void* stream);
 
 /*
  * One whole decoding step of Algorithm 1 (Decoding) -- append (t_K, t_V) to the fp16 residual

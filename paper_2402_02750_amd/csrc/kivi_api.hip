@@ -1,8 +1,10 @@
 // Host side of the C ABI (include/kivi.h): argument validation, split planning, launches.
-// No allocation, no global state, no synchronisation.
+// No allocation, no synchronisation; the only state kept between calls is, per device, the address
+// of the static scratch array below (and the occupancy answers next to the decode kernels).
 #include "kivi_internal.h"
 
 #include <algorithm>
+#include <atomic>
 
 namespace kivi {
 namespace {
@@ -160,14 +162,16 @@ int plan_flush(const kivi_layout_t* l, const kivi_cache_t* c, int32_t policy, in
     return KIVI_OK;
 }
 
-// Host checks shared by the two attention entry points (the cache counts are those the kernel will see).
+// Host checks shared by the attention entry points (the cache counts are those the kernel will see).
+// any_state: the workspace must hold the parts of any cache state of the layout (the documented
+// size); otherwise only a pointer check -- enqueue_attention checks the state's own need.
 int check_attention_args(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, const float* out,
-                         const void* workspace, size_t workspace_bytes) {
+                         const void* workspace, size_t workspace_bytes, bool any_state = true) {
     if (!q || !out || !aligned16(q) || !aligned16(out)) return KIVI_ERR_INVALID_ARG;
     const int length = c->n_kq + c->n_kr;
     if (length < 1 || length != c->n_vq + c->n_vr) return KIVI_ERR_INVALID_ARG;
     size_t need = 0;
-    kivi_decode_workspace_bytes(l, &need);
+    if (any_state) kivi_decode_workspace_bytes(l, &need);
     if (!workspace || !aligned16(workspace) || workspace_bytes < need) return KIVI_ERR_WORKSPACE;
     return KIVI_OK;
 }
@@ -340,6 +344,39 @@ int for_each_run(const kivi_layout_t* l, const kivi_cache_t* c, kivi_seq_state_t
 
 }  // namespace
 
+// ---- kivi_decode_attention_static: the attention workspace as an array inside the library ----
+// For callers that cannot allocate.  Every device the library runs on holds its own copy of the
+// array at its own address; in host code the array's name is only a handle for
+// hipGetSymbolAddress, the kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[KIVI_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxScratchDevices = 64;
+std::atomic<void*> scratch_ptr[kMaxScratchDevices];
+
+// Address of `scratch` on the current device: resolved once per device (with that device
+// current), kept afterwards.
+int static_scratch_address(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return KIVI_ERR_HIP;
+    if (dev < 0 || dev >= kMaxScratchDevices) return KIVI_ERR_UNSUPPORTED;
+    void* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return KIVI_ERR_HIP;
+        scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return KIVI_OK;
+}
+
+__global__ void zero_words_kernel(uint32_t* dst, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0u;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* kivi_status_string(int status) {
@@ -506,6 +543,27 @@ int kivi_decode_attention(const kivi_layout_t* l, const kivi_cache_t* c, const v
     if (int s = check_cache(l, c)) return s;
     if (int s = check_attention_args(l, c, q, out, workspace, workspace_bytes)) return s;
     return enqueue_attention(l, c, q, softmax_scale, out, workspace, workspace_bytes, nullptr, nullptr, stream);
+}
+
+int kivi_decode_attention_static(const kivi_layout_t* l, const kivi_cache_t* c, const void* q,
+                                 float softmax_scale, float* out, void* stream) {
+    if (int s = check_layout(l)) return s;
+    if (int s = check_cache(l, c)) return s;
+    // argument checks first (they need no device); the workspace pointer is not known yet, an aligned
+    // dummy stands in for it
+    if (int s = check_attention_args(l, c, q, out, reinterpret_cast<const void*>(uintptr_t{256}),
+                                     KIVI_STATIC_WORKSPACE_BYTES, false)) return s;
+    void* ws = nullptr;
+    if (int s = static_scratch_address(&ws)) return s;
+    // The array keeps what the last call on this device left.  The parts are written before they are
+    // read; the counters at its start must be zero: a completed call leaves them so, a fill kernel
+    // (not a memset, so that the call can be captured into a graph) makes sure.
+    if (counter_bytes(l) > KIVI_STATIC_WORKSPACE_BYTES) return KIVI_ERR_WORKSPACE;
+    const int n_words = (int)(counter_bytes(l) / sizeof(uint32_t));
+    zero_words_kernel<<<(n_words + 255) / 256, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<uint32_t*>(ws), n_words);
+    if (int s = hip_status(hipGetLastError())) return s;
+    // enqueue_attention refuses (KIVI_ERR_WORKSPACE, nothing launched) a state whose counters and parts pass the limit
+    return enqueue_attention(l, c, q, softmax_scale, out, ws, KIVI_STATIC_WORKSPACE_BYTES, nullptr, nullptr, stream);
 }
 
 int kivi_decode_step(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new, const void* v_new, const void* q,

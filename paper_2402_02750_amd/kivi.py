@@ -30,7 +30,9 @@ EXPORTS = [
     "kivi_quantize_key_groups", "kivi_quantize_value_tokens", "kivi_prefill", "kivi_append_residual",
     "kivi_flush_residual", "kivi_decode_attention", "kivi_decode_step", "kivi_stream_read_probe",
     "kivi_batch_slice", "kivi_decode_step_ragged", "kivi_decode_attention_ragged",
+    "kivi_decode_attention_static",
 ]
+KIVI_STATIC_WORKSPACE_BYTES = 8 << 20
 
 
 class KiviError(RuntimeError):
@@ -93,6 +95,7 @@ def load_library() -> ctypes.CDLL:
     lib.kivi_flush_residual.argtypes = [P(kivi_layout_t), P(kivi_cache_t), I32, P(I32), P(I32), VP]
     lib.kivi_decode_attention.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, ctypes.c_float,
                                           VP, VP, ctypes.c_size_t, VP]
+    lib.kivi_decode_attention_static.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, ctypes.c_float, VP, VP]
     lib.kivi_decode_step.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, VP, VP, ctypes.c_float, I32,
                                      VP, VP, ctypes.c_size_t, VP]
     lib.kivi_stream_read_probe.argtypes = [VP, ctypes.c_size_t, VP, VP]
@@ -250,6 +253,16 @@ def kivi_decode_attention(layout, cache: Cache, q_fp16, softmax_scale, out_fp32,
         ctypes.c_float(softmax_scale), ctypes.c_void_p(out_fp32.data_ptr()),
         ctypes.c_void_p(cache.workspace.data_ptr()), cache.workspace.numel(),
         _stream_handle(stream)), "kivi_decode_attention")
+    return out_fp32
+
+
+def kivi_decode_attention_static(layout, cache, q_fp16, softmax_scale, out_fp32, stream=None):
+    """kivi_decode_attention on the library's static workspace (no allocation, no workspace argument)."""
+    assert q_fp16.is_contiguous() and out_fp32.is_contiguous()
+    _check(load_library().kivi_decode_attention_static(
+        ctypes.byref(layout), ctypes.byref(cache.c), ctypes.c_void_p(q_fp16.data_ptr()),
+        ctypes.c_float(softmax_scale), ctypes.c_void_p(out_fp32.data_ptr()), _stream_handle(stream)),
+        "kivi_decode_attention_static")
     return out_fp32
 
 
