@@ -110,8 +110,7 @@ SplitPlan plan_splits(const kivi_layout_t* l, const kivi_cache_t* c, bool mfma, 
 
 int hip_status(hipError_t e) { return e == hipSuccess ? KIVI_OK : KIVI_ERR_HIP; }
 
-int enqueue_key_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens,
-                      hipStream_t hs) {
+QuantKeyParams key_quant_params(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens) {
     QuantKeyParams p{};
     p.src = src;
     p.codes = static_cast<uint32_t*>(c->k_codes);
@@ -120,11 +119,10 @@ int enqueue_key_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSo
     p.n_kv_heads = l->n_kv_heads; p.cap_tiles = l->cap_q_tokens / kTileTokens; p.bits = l->bits;
     p.first_tile = c->n_kq / kTileTokens; p.n_tiles = n_tokens / kTileTokens; p.batch = l->batch;
     p.tiles_per_group = l->group / kTileTokens;
-    return hip_status(launch_quantize_keys(p, hs));
+    return p;
 }
 
-int enqueue_value_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens,
-                        hipStream_t hs) {
+QuantValueParams value_quant_params(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens) {
     QuantValueParams p{};
     p.src = src;
     p.codes = static_cast<uint32_t*>(c->v_codes);
@@ -133,7 +131,17 @@ int enqueue_value_quant(const kivi_layout_t* l, const kivi_cache_t* c, const Row
     p.n_kv_heads = l->n_kv_heads; p.cap_tiles = l->cap_q_tokens / kTileTokens; p.bits = l->bits;
     p.first_token = c->n_vq; p.n_tokens = n_tokens; p.batch = l->batch;
     p.group_blocks = l->group / kTileTokens;
-    return hip_status(launch_quantize_values(p, hs));
+    return p;
+}
+
+int enqueue_key_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens,
+                      hipStream_t hs) {
+    return hip_status(launch_quantize_keys(key_quant_params(l, c, src, n_tokens), hs));
+}
+
+int enqueue_value_quant(const kivi_layout_t* l, const kivi_cache_t* c, const RowSource& src, int n_tokens,
+                        hipStream_t hs) {
+    return hip_status(launch_quantize_values(value_quant_params(l, c, src, n_tokens), hs));
 }
 
 }  // namespace
@@ -159,6 +167,21 @@ int plan_flush(const kivi_layout_t* l, const kivi_cache_t* c, int32_t policy, in
         return KIVI_ERR_INVALID_ARG;
     *n_key = nk;
     *n_value = nv;
+    return KIVI_OK;
+}
+
+// Quantise the oldest nk residual keys and nv residual values out of the rings (one launch; either
+// count may be 0) and advance the cache counters (`launch` false: the counters only).
+int enqueue_flush(const kivi_layout_t* l, kivi_cache_t* c, int nk, int nv, hipStream_t hs, bool launch = true) {
+    const int64_t sh = (int64_t)l->cap_r_tokens * kHeadDim, sb = sh * l->n_kv_heads;
+    if (launch && (nk > 0 || nv > 0)) {
+        const RowSource ksrc{static_cast<const __half*>(c->k_resid), sb, sh, kHeadDim, c->k_r_start, l->cap_r_tokens};
+        const RowSource vsrc{static_cast<const __half*>(c->v_resid), sb, sh, kHeadDim, c->v_r_start, l->cap_r_tokens};
+        if (int s = hip_status(launch_flush_quantize(key_quant_params(l, c, ksrc, nk), value_quant_params(l, c, vsrc, nv), hs)))
+            return s;
+    }
+    c->n_kq += nk; c->n_kr -= nk; c->k_r_start = (c->k_r_start + nk) % l->cap_r_tokens;
+    c->n_vq += nv; c->n_vr -= nv; c->v_r_start = (c->v_r_start + nv) % l->cap_r_tokens;
     return KIVI_OK;
 }
 
@@ -254,9 +277,11 @@ int head_split_shift(const kivi_layout_t* l, const SplitPlan& plan, int path, bo
 
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the
 // rows of token length-1 are not in the rings yet and the (matrix-core) kernel puts them there.
+// flush_k / flush_v non-null (two-launch form only): the residual flush that produced state `c` has
+// not been launched yet; the fp16-row launch carries it out with extra workgroups.
 int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void* q, float softmax_scale,
                       float* out, void* workspace, size_t workspace_bytes, const void* k_new, const void* v_new,
-                      void* stream) {
+                      void* stream, const QuantKeyParams* flush_k = nullptr, const QuantValueParams* flush_v = nullptr) {
     const int length = c->n_kq + c->n_kr;
     DecodeParams p{};
     p.k_codes = static_cast<const uint32_t*>(c->k_codes);
@@ -280,6 +305,9 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     const bool two = wants_two_launches(l, c, path);
     p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
     p.two_launches = two ? 1 : 0;
+    if ((flush_k || flush_v) && !(two && flush_k && flush_v)) return KIVI_ERR_INVALID_ARG;
+    p.flush_k = flush_k;
+    p.flush_v = flush_v;
     const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
     if (counter_bytes(l) + rows * (kHeadDim + 2) * sizeof(float) > workspace_bytes) return KIVI_ERR_WORKSPACE;
     p.counters = static_cast<int32_t*>(workspace);
@@ -307,6 +335,8 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
         if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
         if (int s = hip_status(e)) return s;
         p.k_new = p.v_new = nullptr;
+        p.flush_k = nullptr;
+        p.flush_v = nullptr;
     }
     // the matrix-core kernel merges its splits itself; the vector-ALU family uses a second launch
     return path == KIVI_DECODE_MFMA ? KIVI_OK : hip_status(launch_merge(p, hs));
@@ -482,18 +512,7 @@ int kivi_flush_residual(const kivi_layout_t* l, kivi_cache_t* c, int32_t policy,
     if (policy != KIVI_FLUSH_WINDOW && policy != KIVI_FLUSH_ALG1) return KIVI_ERR_INVALID_ARG;
     int nk = 0, nv = 0;
     if (int s = plan_flush(l, c, policy, &nk, &nv)) return s;
-    const int64_t sh = (int64_t)l->cap_r_tokens * kHeadDim, sb = sh * l->n_kv_heads;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (nk > 0) {
-        const RowSource src{static_cast<const __half*>(c->k_resid), sb, sh, kHeadDim, c->k_r_start, l->cap_r_tokens};
-        if (int s = enqueue_key_quant(l, c, src, nk, hs)) return s;
-    }
-    if (nv > 0) {
-        const RowSource src{static_cast<const __half*>(c->v_resid), sb, sh, kHeadDim, c->v_r_start, l->cap_r_tokens};
-        if (int s = enqueue_value_quant(l, c, src, nv, hs)) return s;
-    }
-    c->n_kq += nk; c->n_kr -= nk; c->k_r_start = (c->k_r_start + nk) % l->cap_r_tokens;
-    c->n_vq += nv; c->n_vr -= nv; c->v_r_start = (c->v_r_start + nv) % l->cap_r_tokens;
+    if (int s = enqueue_flush(l, c, nk, nv, static_cast<hipStream_t>(stream))) return s;
     if (n_key_flushed) *n_key_flushed = nk;
     if (n_value_flushed) *n_value_flushed = nv;
     return KIVI_OK;
@@ -586,11 +605,35 @@ int kivi_decode_step(const kivi_layout_t* l, kivi_cache_t* c, const void* k_new,
         fl.n_kq += nk; fl.n_kr -= nk; fl.n_vq += nv; fl.n_vr -= nv;
         if (int s = check_attention_args(l, &fl, q, out, workspace, workspace_bytes)) return s;
     }
-    if (nk == 0 && nv == 0 && decode_family(l) == KIVI_DECODE_MFMA) {
+    if (decode_family(l) == KIVI_DECODE_MFMA && nk <= c->n_kr && nv <= c->n_vr) {
+        // The tokens to flush were all in the rings before this step: quantise them first (one
+        // launch, none on the steps without a flush), then let the attention read the new token from
+        // k_new / v_new and store it in the rings itself.  The ring slot of the new token and the
+        // cache state seen by the attention are the same as with append -> flush -> attention.
+        kivi_cache_t flushed = *c;                       // the counters after the flush, nothing launched yet
+        if (int s = enqueue_flush(l, &flushed, nk, nv, nullptr, false)) return s;
+        after = flushed;
+        after.n_kr += 1;
+        after.n_vr += 1;
+        // In the two-launch form (G = 32) the fp16-row launch quantises the flushed tokens with extra
+        // workgroups: a flush step then takes two launches like any other step.
+        if ((nk > 0 || nv > 0) && l->group == kTileTokens && wants_two_launches(l, &after, KIVI_DECODE_MFMA)) {
+            const int64_t sh = (int64_t)l->cap_r_tokens * kHeadDim, sb = sh * l->n_kv_heads;
+            const RowSource ksrc{static_cast<const __half*>(c->k_resid), sb, sh, kHeadDim, c->k_r_start, l->cap_r_tokens};
+            const RowSource vsrc{static_cast<const __half*>(c->v_resid), sb, sh, kHeadDim, c->v_r_start, l->cap_r_tokens};
+            const QuantKeyParams kp = key_quant_params(l, c, ksrc, nk);
+            const QuantValueParams vp = value_quant_params(l, c, vsrc, nv);
+            if (int s = enqueue_attention(l, &after, q, softmax_scale, out, workspace, workspace_bytes, k_new, v_new, stream, &kp, &vp))
+                return s;
+            *c = after;
+            return KIVI_OK;
+        }
+        if (int s = enqueue_flush(l, c, nk, nv, static_cast<hipStream_t>(stream))) return s;
         if (int s = enqueue_attention(l, &after, q, softmax_scale, out, workspace, workspace_bytes, k_new, v_new, stream)) return s;
         *c = after;
         return KIVI_OK;
     }
+    // the flush takes the new token itself (Algorithm 1's key flush, or no residual window): append first
     if (int s = kivi_append_residual(l, c, k_new, v_new, stream)) return s;
     if (int s = kivi_flush_residual(l, c, policy, nullptr, nullptr, stream)) return s;
     return enqueue_attention(l, c, q, softmax_scale, out, workspace, workspace_bytes, nullptr, nullptr, stream);

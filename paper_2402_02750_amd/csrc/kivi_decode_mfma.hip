@@ -38,6 +38,10 @@
 #include <algorithm>
 #include <atomic>
 
+#ifndef KIVI_EARLY_REP
+#define KIVI_EARLY_REP 2
+#endif
+
 namespace kivi {
 namespace {
 
@@ -751,16 +755,25 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // accumulators and the registers of an in-flight quantised chunk do not fit side by side.
     // Every unit touched here gets a part of its own (merged with the other parts of the unit by
     // whichever workgroup finishes the unit last).
-    auto initial_request = [&]() {
+    // The first all-quantised chunk's key-side data is requested before the fp16-row phase where the
+    // registers allow it (one or two query heads per kv-head): it then travels while that phase
+    // runs; the value-side data follows when the phase has freed its row registers.
+    constexpr bool kEarlyKeys = MODE == kBothPhases && REP <= KIVI_EARLY_REP;
+    auto initial_request_keys = [&]() {
         if (first_a < last_a) {
             set_next(first_a, true);
             request_zero_rows();
 #pragma unroll
             for (int i = 0; i < kSlots; ++i) request_key_slot(i);
+        }
+    };
+    auto initial_request_values = [&]() {
+        if (first_a < last_a) {
 #pragma unroll
             for (int i = 0; i < kSlots; ++i) request_value_slot(i);
         }
     };
+    if constexpr (kEarlyKeys) initial_request_keys();
     // A unit's phase-1 part is parked in LDS if this workgroup is the unit's only contributor in both
     // phases and a slot is free; phase 2 meets the parked units in the same order.
     int n_held = 0, n_popped = 0;
@@ -978,7 +991,8 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     if constexpr (MODE == kQuantisedOnly) {         // the first query ahead of the first chunk: loads return in order
         if (first_a < last_a) request_q(first_a / n_a);
     }
-    initial_request();                              // overlaps the merge of the last fp16-row unit
+    if constexpr (!kEarlyKeys) initial_request_keys();
+    initial_request_values();                       // overlaps the merge of the last fp16-row unit
     // If the last unit of phase 1 is the first unit of phase 2 and no other workgroup touches it, its
     // running state simply carries over: no part, no merge.
     bool carry = false;
@@ -1112,7 +1126,12 @@ hipError_t launch_two(DecodeParams p, hipStream_t stream) {
     const int64_t units = (int64_t)p.batch * p.n_kv_heads;
     const int64_t total_a = units * p.plan.n_splits_a;
     if (total_a > 0x3fffffff) return hipErrorInvalidValue;
-    if (hipError_t e = launch_residual_rows(p, stream); e != hipSuccess) return e;
+    // (with a residual flush to carry out, the first launch also quantises the flushed tokens)
+    if (hipError_t e = p.flush_k ? launch_rows_and_flush(p, *p.flush_k, *p.flush_v, stream) : launch_residual_rows(p, stream);
+        e != hipSuccess)
+        return e;
+    p.flush_k = nullptr;
+    p.flush_v = nullptr;
     p.k_new = p.v_new = nullptr;                   // the first launch has stored the new token's rows
     p.total_chunks_a = (int)total_a;
     p.total_chunks_b = 0;

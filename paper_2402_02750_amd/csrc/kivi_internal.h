@@ -106,6 +106,10 @@ struct DecodeParams {
     // > 0: the matrix-core family runs as two launches (fp16 rows, then the all-quantised chunks); the
     // plan then has a single fp16-row split per unit (n_splits_b == 1).
     int32_t two_launches;
+    // Host side only (two-launch form): the residual flush of this decode step, to be carried out by
+    // extra workgroups of the fp16-row launch instead of a launch of its own; null otherwise.
+    const QuantKeyParams* flush_k;
+    const QuantValueParams* flush_v;
     // k > 0 (single launch, 4, 6 or 8 query heads per kv-head, small batches): every kv-head's query
     // heads are served as 2^k equal parts, each a unit of its own on the instantiation for one part
     // (rep_variant 2 or 4, rep_here = heads of a part); the cache is read once per part.
@@ -115,10 +119,15 @@ struct DecodeParams {
 // launchers (each defined next to its kernels); they return hipGetLastError() after the launch
 hipError_t launch_quantize_keys(const QuantKeyParams& p, hipStream_t stream);
 hipError_t launch_quantize_values(const QuantValueParams& p, hipStream_t stream);
+// key groups and value tokens of one residual flush in a single launch (either part may be empty)
+hipError_t launch_flush_quantize(const QuantKeyParams& kp, const QuantValueParams& vp, hipStream_t stream);
 hipError_t launch_copy_rows(const CopyRowsParams& p, hipStream_t stream);
 hipError_t launch_decode_valu(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_residual_rows(const DecodeParams& p, hipStream_t stream);
+// the same launch with extra workgroups that quantise the key group(s) and value tokens of a residual
+// flush (G = 32 only: hipErrorNotSupported otherwise, nothing launched)
+hipError_t launch_rows_and_flush(const DecodeParams& p, const QuantKeyParams& kp, const QuantValueParams& vp, hipStream_t stream);
 // whether launch_residual_rows serves `tiles_b` tiles of fp16 rows on the instantiation for `rep_variant` heads
 bool residual_rows_possible(int tiles_b, int rep_variant);
 hipError_t launch_merge(const DecodeParams& p, hipStream_t stream);

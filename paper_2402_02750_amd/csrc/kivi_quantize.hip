@@ -9,9 +9,11 @@
 // the two to differ.  This file is compiled with -ffp-contract=off, so the only fused operations
 // are the ones written as fmaf().
 #include "kivi_internal.h"
+#include "kivi_rows_block.h"
 
 #include <hip/hip_fp16.h>
 
+#include <algorithm>
 #include <type_traits>
 
 namespace kivi {
@@ -133,18 +135,22 @@ __device__ __forceinline__ void word_coords(int wd, int bit, int& lane, int& u, 
 // One workgroup quantises one key group: TG tiles of 32 tokens (G = 32 * TG tokens per group).
 // Scale and zero-point rows are stored once per tile, i.e. replicated TG times: the decode kernels
 // read them at tile granularity whatever G is.
+// (A device function so that it can also run as a role of a wider launch: group g of kv-head h of
+// batch entry b; 256 threads work, any further threads of the workgroup only keep the barriers.)
 template <int BITS, int TG>
-__global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
+__device__ __forceinline__ void quantize_key_block(const QuantKeyParams& p, int g, int h, int b, int tid) {
     constexpr int kRows = TG * kTileTokens;
     __shared__ __align__(16) __half tile[kRows][kRowPad];
     __shared__ __align__(16) float sh_y[kHeadDim], sh_c0[kHeadDim], sh_z[kHeadDim], sh_s[kHeadDim];
     __shared__ float sh_tol[4];         // per wavefront: largest fast-path tolerance of its groups
     __shared__ half2v sh_lo[4][kHeadDim / 2], sh_hi[4][kHeadDim / 2];
-    const int g = blockIdx.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const bool active = tid < 256;
     constexpr float levels = (float)((1 << BITS) - 1);
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
 
-    if (p.src.ring_cap > 0) {
+    if (!active) {
+        // nothing to load
+    } else if (p.src.ring_cap > 0) {
 #pragma unroll
         for (int pass = 0; pass < 2 * TG; ++pass) {
             const int row = pass * 16 + (tid >> 4), seg = tid & 15;
@@ -166,7 +172,7 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
     // Group minimum / maximum with all 256 threads: wavefront w scans a quarter of the group's
     // tokens for a channel pair with packed fp16 min / max (exact: no arithmetic), then 128 threads
     // combine the four partial results of their channel.
-    {
+    if (active) {
         const int cp = tid & 63, tq = tid >> 6;
         half2v lo2 = *reinterpret_cast<const half2v*>(&tile[tq * (kRows / 4)][2 * cp]), hi2 = lo2;
 #pragma unroll
@@ -209,7 +215,7 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
     // consecutive channels: read each run from LDS as one vector (2-byte reads of a column of
     // 16-byte-aligned rows hit only every fourth bank) and the group constants of the run once.
     constexpr int RUN = 16 / BITS;
-    for (int wi = tid; wi < TG * kWords; wi += 256) {
+    for (int wi = active ? tid : TG * kWords; wi < TG * kWords; wi += 256) {
         const int ti = wi / kWords, wd = wi % kWords;
         int lane, c0;
         if (BITS == 2) {
@@ -259,19 +265,21 @@ __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
     }
 }
 
+// One workgroup quantises kValueTilesPerGroup consecutive value tiles (block index bx along the
+// tiles).  A device function for the same reason as quantize_key_block.
 template <int BITS>
-__global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p) {
+__device__ __forceinline__ void quantize_value_block(const QuantValueParams& p, int bx, int h, int b, int tid) {
     __shared__ __align__(16) __half tile[kTileTokens][kRowPad];
     __shared__ GroupConst sh_g[kTileTokens][4];
     __shared__ float2 sh_mm[kTileTokens][4];    // per (token, 32-channel block): group minimum, maximum
     __shared__ float sh_tol[4];         // per wavefront: largest fast-path tolerance of its groups
-    const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const bool active = tid < 256;
     constexpr float levels = (float)((1 << BITS) - 1);
     const int64_t unit = (int64_t)b * p.n_kv_heads + h;
     // kValueTilesPerGroup consecutive destination tiles per workgroup, next tile's rows prefetched
     const int first_tile = p.first_token / kTileTokens;
     const int n_tiles = (p.first_token + p.n_tokens - 1) / kTileTokens - first_tile + 1;
-    const int i_lo = blockIdx.x * kValueTilesPerGroup, i_hi = min(i_lo + kValueTilesPerGroup, n_tiles);
+    const int i_lo = bx * kValueTilesPerGroup, i_hi = min(i_lo + kValueTilesPerGroup, n_tiles);
     uint4 rows[2];
     auto request = [&](int i) {
         const int dt = first_tile + i;
@@ -281,7 +289,7 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         for (int pass = 0; pass < 2; ++pass) {
             const int row = pass * 16 + (tid >> 4), seg = tid & 15;
             rows[pass] = uint4{0u, 0u, 0u, 0u};
-            if (row >= lo && row < hi)
+            if (active && row >= lo && row < hi)
                 rows[pass] = *reinterpret_cast<const uint4*>(
                     p.src.base + row_offset(p.src, b, h, dt * kTileTokens + row - p.first_token) + seg * 8);
         }
@@ -292,16 +300,18 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
     // destination tokens of this tile that this call writes: [lo, hi) within the tile
     const int lo_tok = max(p.first_token - dst_tile * kTileTokens, 0);
     const int hi_tok = min(p.first_token + p.n_tokens - dst_tile * kTileTokens, kTileTokens);
+    if (active) {
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass)
-        *reinterpret_cast<uint4*>(&tile[pass * 16 + (tid >> 4)][(tid & 15) * 8]) = rows[pass];
+        for (int pass = 0; pass < 2; ++pass)
+            *reinterpret_cast<uint4*>(&tile[pass * 16 + (tid >> 4)][(tid & 15) * 8]) = rows[pass];
+    }
     __syncthreads();
     if (i + 1 < i_hi) request(i + 1);
     const bool full = (lo_tok == 0 && hi_tok == kTileTokens);
 
     // Group minimum / maximum with all 256 threads: two threads per (token, channel group), each
     // reduces 16 channels with packed fp16 min / max (exact), partner lanes combine.
-    {
+    if (active) {
         const int t = tid >> 3, cg = (tid >> 1) & 3, part = tid & 1;
         union { uint4 v; half2v h[4]; } a, c;
         a.v = *reinterpret_cast<const uint4*>(&tile[t][cg * 32 + part * 16]);
@@ -392,12 +402,53 @@ __global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p
         }
     };
     if (full) {
-        for (int wd = tid; wd < kWords; wd += 256) encode_word(wd, std::true_type{});
+        for (int wd = active ? tid : kWords; wd < kWords; wd += 256) encode_word(wd, std::true_type{});
     } else {
-        for (int wd = tid; wd < kWords; wd += 256) encode_word(wd, std::false_type{});
+        for (int wd = active ? tid : kWords; wd < kWords; wd += 256) encode_word(wd, std::false_type{});
     }
     __syncthreads();          // the tile and the group constants are overwritten by the next tile
     }
+}
+
+template <int BITS, int TG>
+__global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
+    quantize_key_block<BITS, TG>(p, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_values_kernel(QuantValueParams p) {
+    quantize_value_block<BITS>(p, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
+}
+
+// A residual flush in one launch: the first n_key_blocks workgroups along x quantise key groups, the
+// others value tiles (Algorithm 1, Decoding: both residual parts are flushed in the same step).
+template <int BITS, int TG>
+__global__ __launch_bounds__(256) void flush_quantize_kernel(QuantKeyParams kp, QuantValueParams vp, int n_key_blocks) {
+    if ((int)blockIdx.x < n_key_blocks) quantize_key_block<BITS, TG>(kp, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
+    else quantize_value_block<BITS>(vp, (int)blockIdx.x - n_key_blocks, blockIdx.y, blockIdx.z, threadIdx.x);
+}
+
+// The first launch of a two-launch decode step that also flushes (Algorithm 1, Decoding): workgroups
+// [0, units) serve the fp16 rows of one (batch, kv-head) unit each -- the rows that stay in the window
+// -- and the following ones quantise, per unit, the key group and the value tokens that leave it.
+// The two kinds touch disjoint memory; the launch of the all-quantised chunks that follows sees both
+// results.  The workgroup size is the larger of the two roles' (the surplus threads idle).
+template <int REP, int BITS>
+__global__ __launch_bounds__(1024) void rows_flush_kernel(DecodeParams p, QuantKeyParams kp, QuantValueParams vp,
+                                                          int tiles_b, int n_key_blocks, int n_value_blocks) {
+    extern __shared__ float sm_dyn[];
+    const int64_t units = (int64_t)p.batch * p.n_kv_heads;
+    int64_t bx = blockIdx.x;
+    if (bx < units) {
+        rows::residual_rows_block<REP>(p, sm_dyn, bx, tiles_b, threadIdx.x);
+        return;
+    }
+    bx -= units;
+    const int per_unit = n_key_blocks + n_value_blocks;
+    const int unit = (int)(bx / per_unit), r = (int)(bx % per_unit);
+    const int h = unit % kp.n_kv_heads, b = unit / kp.n_kv_heads;
+    if (r < n_key_blocks) quantize_key_block<BITS, 1>(kp, r, h, b, threadIdx.x);
+    else quantize_value_block<BITS>(vp, r - n_key_blocks, h, b, threadIdx.x);
 }
 
 __global__ __launch_bounds__(256) void copy_rows_kernel(CopyRowsParams p) {
@@ -473,6 +524,57 @@ hipError_t launch_quantize_values(const QuantValueParams& p, hipStream_t stream)
     dim3 grid((last_tile - first_tile + kValueTilesPerGroup) / kValueTilesPerGroup, p.n_kv_heads, p.batch), block(256);
     if (p.bits == 2) quantize_values_kernel<2><<<grid, block, 0, stream>>>(p);
     else quantize_values_kernel<4><<<grid, block, 0, stream>>>(p);
+    return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t launch_flush_bits(const QuantKeyParams& kp, const QuantValueParams& vp, hipStream_t stream) {
+    const int tg = kp.tiles_per_group;
+    if (kp.n_tiles % tg != 0) return hipErrorInvalidValue;
+    const int n_key_blocks = kp.n_tiles / tg;
+    const int first_tile = vp.first_token / kTileTokens, last_tile = (vp.first_token + vp.n_tokens - 1) / kTileTokens;
+    const int n_value_blocks = (last_tile - first_tile + kValueTilesPerGroup) / kValueTilesPerGroup;
+    dim3 grid(n_key_blocks + n_value_blocks, kp.n_kv_heads, kp.batch), block(256);
+    if (tg == 1) flush_quantize_kernel<BITS, 1><<<grid, block, 0, stream>>>(kp, vp, n_key_blocks);
+    else if (tg == 2) flush_quantize_kernel<BITS, 2><<<grid, block, 0, stream>>>(kp, vp, n_key_blocks);
+    else if (tg == 4) flush_quantize_kernel<BITS, 4><<<grid, block, 0, stream>>>(kp, vp, n_key_blocks);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_flush_quantize(const QuantKeyParams& kp, const QuantValueParams& vp, hipStream_t stream) {
+    if (kp.n_tiles <= 0) return launch_quantize_values(vp, stream);
+    if (vp.n_tokens <= 0) return launch_quantize_keys(kp, stream);
+    return kp.bits == 2 ? launch_flush_bits<2>(kp, vp, stream) : launch_flush_bits<4>(kp, vp, stream);
+}
+
+hipError_t launch_rows_and_flush(const DecodeParams& p, const QuantKeyParams& kp, const QuantValueParams& vp,
+                                 hipStream_t stream) {
+    const int tiles_b = p.plan.tiles_total - p.plan.tiles_a;
+    const int64_t units = (int64_t)p.batch * p.n_kv_heads;
+    const int rep = p.rep_variant <= 2 ? p.rep_variant : (p.rep_variant <= 4 ? 4 : 8);
+    if (kp.tiles_per_group != 1 || vp.group_blocks != 1) return hipErrorNotSupported;
+    if (!residual_rows_possible(tiles_b, rep) || p.plan.n_splits_b != 1 || p.n_kq != p.n_vq) return hipErrorInvalidValue;
+    if (kp.bits != vp.bits || kp.n_tiles < 0 || vp.n_tokens < 0 || kp.n_tiles + vp.n_tokens <= 0) return hipErrorInvalidValue;
+    const int n_key_blocks = kp.n_tiles;
+    int n_value_blocks = 0;
+    if (vp.n_tokens > 0) {
+        const int first_tile = vp.first_token / kTileTokens, last_tile = (vp.first_token + vp.n_tokens - 1) / kTileTokens;
+        n_value_blocks = (last_tile - first_tile + kValueTilesPerGroup) / kValueTilesPerGroup;
+    }
+    const int64_t blocks = units * (1 + n_key_blocks + n_value_blocks);
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(std::max(256, 64 * tiles_b));
+    const size_t lds = rows::rows_lds_bytes(tiles_b, rep);
+    auto go = [&](auto rep_tag) {
+        constexpr int R = decltype(rep_tag)::value;
+        if (kp.bits == 2) rows_flush_kernel<R, 2><<<grid, block, lds, stream>>>(p, kp, vp, tiles_b, n_key_blocks, n_value_blocks);
+        else rows_flush_kernel<R, 4><<<grid, block, lds, stream>>>(p, kp, vp, tiles_b, n_key_blocks, n_value_blocks);
+    };
+    if (rep == 1) go(std::integral_constant<int, 1>{});
+    else if (rep == 2) go(std::integral_constant<int, 2>{});
+    else if (rep == 4) go(std::integral_constant<int, 4>{});
+    else go(std::integral_constant<int, 8>{});
     return hipGetLastError();
 }
 
