@@ -289,11 +289,20 @@ int kivi_batch_slice(const kivi_layout_t* layout, const kivi_cache_t* cache, int
 /*
  * kivi_decode_step / kivi_decode_attention for a batch whose sequences differ in length.  The
  * integer fields of `cache` are ignored; `states` (host, [batch]) is read and, by the step,
- * advanced.  The batch is walked in runs of consecutive entries with equal state and each run is
- * one call of the uniform entry point on that part of the batch (same stream, same workspace): a
- * batch sorted by length, or one in which many sequences share a length, takes few launches; a
- * batch of B different lengths takes B.  Entries without any token (all counts 0) are skipped by
- * kivi_decode_attention_ragged and their `out` rows are left untouched.
+ * advanced.
+ *   One pair of launches for the whole batch, whatever the lengths: when the matrix-core family
+ * serves the layout (decode_path AUTO, MFMA or MFMA_TWO), every sequence has K and V split alike
+ * (the WINDOW policy) with 1 to 512 fp16 rows (at most 16 tiles; fewer with many query heads per
+ * kv-head), and at least one sequence has quantised tokens.  The fp16 rows of all sequences run in
+ * one launch (which also appends the step's new tokens), the all-quantised parts in a second; both
+ * read each sequence's counters from a copy in the workspace, and the shorter sequences' share of
+ * the work partition is skipped.  A step adds one launch per run of equal sequences that flush in
+ * it (a sequence flushes every G-th step).
+ *   Otherwise (another policy or family, empty slots, sequences without fp16 rows) the batch is
+ * walked in runs of consecutive entries with equal state and each run is one call of the uniform
+ * entry point on that part of the batch (same stream, same workspace): B different lengths take B
+ * calls.  Entries without any token (all counts 0) are skipped by kivi_decode_attention_ragged and
+ * their `out` rows are left untouched.  kivi_decode_launches_ragged tells which applies.
  *   k_new, v_new, q, out   the whole batch's tensors, as for the uniform entry points
  * Errors: as for the uniform entry points; entries before the failing run have been processed.
  */
@@ -303,6 +312,14 @@ int kivi_decode_step_ragged(const kivi_layout_t* layout, const kivi_cache_t* cac
 int kivi_decode_attention_ragged(const kivi_layout_t* layout, const kivi_cache_t* cache,
                                  const kivi_seq_state_t* states, const void* q, float softmax_scale, float* out,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Host helper: the number of kernel launches kivi_decode_attention_ragged enqueues for these
+ * sequence states (no launch).  Two per group of up to 8 query heads per kv-head when the whole batch
+ * goes through one pair of launches (see above); otherwise the sum over the runs of equal state.
+ * Errors: INVALID_ARG, UNSUPPORTED.
+ */
+int kivi_decode_launches_ragged(const kivi_layout_t* layout, const kivi_seq_state_t* states, int32_t* launches);
 
 /*
  * Measurement helper, not part of the method: a plain read-only stream over `bytes` bytes of

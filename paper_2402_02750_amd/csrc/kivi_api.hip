@@ -60,6 +60,12 @@ size_t counter_bytes(const kivi_layout_t* l) {
     return ((size_t)l->batch * l->n_kv_heads * 4 * sizeof(int32_t) + 255) / 256 * 256;
 }
 
+// Room for the per-sequence counters of a batch of different lengths (16 bytes per sequence, padded
+// to 256 bytes); the ragged entry points keep them behind the split counters.
+size_t seq_state_bytes(const kivi_layout_t* l) {
+    return ((size_t)l->batch * 4 * sizeof(int32_t) + 255) / 256 * 256;
+}
+
 // Upper bound of the number of context splits for any cache state of this layout.
 // Both planners below give every all-quantised split at least 4 tiles (the matrix-core family 8 or
 // 16), and every split with fp16 rows at least one tile; enqueue_attention checks the actual count
@@ -374,6 +380,166 @@ int for_each_run(const kivi_layout_t* l, const kivi_cache_t* c, kivi_seq_state_t
 
 }  // namespace
 
+// ---- batches of different lengths in one pair of launches ----
+namespace {
+
+constexpr int kNotApplicable = 1;       // (internal) the fast path does not serve this batch: use the run-by-run path
+
+// Attention over a batch whose sequences differ in length as ONE pair of launches of the matrix-core
+// family's two-launch form: the fp16 rows of every unit (which also append the new token when
+// k_new / v_new are given), then the all-quantised chunks.  Both kernels read each sequence's
+// counters from a device array; the split plan is the longest sequence's, a shorter one's surplus
+// chunks and tiles are masked.  Served: K and V split alike in every sequence, at least one fp16
+// row and at most 16 tiles of them per sequence, at least one quantised tile somewhere in the
+// batch.  `st`: the states the attention sees (after append and flush).  Returns kNotApplicable
+// (nothing launched) for any other batch.
+int ragged_attention_fast(const kivi_layout_t* l, const kivi_cache_t* c, const kivi_seq_state_t* st, const void* q,
+                          float softmax_scale, float* out, void* workspace, size_t workspace_bytes,
+                          const void* k_new, const void* v_new, void* stream) {
+    if (decode_family(l) != KIVI_DECODE_MFMA || l->decode_path == KIVI_DECODE_MFMA_ONE) return kNotApplicable;
+    if (l->cap_q_tokens < kTileTokens) return kNotApplicable;
+    const int rep_total = l->n_q_heads / l->n_kv_heads;
+    const int rep_launch = std::min(rep_total, kMaxRep);
+    const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
+    int max_tiles_a = 0, max_tiles_b = 0;
+    for (int b = 0; b < l->batch; ++b) {
+        const kivi_seq_state_t& x = st[b];
+        if (x.n_kq != x.n_vq || x.n_kr != x.n_vr || x.n_kr < 1 || x.n_kq % kTileTokens != 0) return kNotApplicable;
+        const int tiles_a = x.n_kq / kTileTokens;
+        max_tiles_a = std::max(max_tiles_a, tiles_a);
+        max_tiles_b = std::max(max_tiles_b, ceil_div(x.n_kq + x.n_kr, kTileTokens) - tiles_a);
+    }
+    if (max_tiles_a < 1 || !residual_rows_possible(max_tiles_b, rep_variant)) return kNotApplicable;
+    const MfmaGeometry g = mfma_geometry(l->bits, rep_launch);
+    if (g.chunk_tiles == 0) return kNotApplicable;
+
+    DecodeParams p{};
+    p.k_codes = static_cast<const uint32_t*>(c->k_codes);
+    p.k_scale = static_cast<const __half*>(c->k_scale);
+    p.k_zero = static_cast<const __half*>(c->k_zero);
+    p.v_codes = static_cast<const uint32_t*>(c->v_codes);
+    p.v_scale = static_cast<const __half*>(c->v_scale);
+    p.v_zero = static_cast<const __half*>(c->v_zero);
+    p.k_resid = static_cast<const __half*>(c->k_resid);
+    p.v_resid = static_cast<const __half*>(c->v_resid);
+    p.k_new = static_cast<const __half*>(k_new); p.v_new = static_cast<const __half*>(v_new);
+    // the scalar counters describe the longest sequence (the kernels take each sequence's own from seq_state)
+    p.n_kq = p.n_vq = max_tiles_a * kTileTokens;
+    p.n_kr = p.n_vr = max_tiles_b * kTileTokens;
+    p.length = p.n_kq + p.n_kr;
+    p.cap_tiles = l->cap_q_tokens / kTileTokens; p.cap_r = l->cap_r_tokens;
+    p.q = static_cast<const __half*>(q); p.out = out;
+    p.softmax_scale = softmax_scale;
+    p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
+    p.plan.tiles_a = max_tiles_a;
+    p.plan.tiles_total = max_tiles_a + max_tiles_b;
+    p.plan.tiles_per_split_a = g.chunk_tiles;
+    p.plan.tiles_per_split_b = max_tiles_b;
+    p.plan.n_splits_a = ceil_div(max_tiles_a, g.chunk_tiles);
+    p.plan.n_splits_b = 1;
+    p.two_launches = 1;
+    const size_t rows = (size_t)l->batch * l->n_q_heads * p.plan.n_splits();
+    if (counter_bytes(l) + seq_state_bytes(l) + rows * (kHeadDim + 2) * sizeof(float) > workspace_bytes) return KIVI_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    p.counters = reinterpret_cast<int32_t*>(ws);
+    int32_t* dev_state = reinterpret_cast<int32_t*>(ws + counter_bytes(l));
+    p.seq_state = dev_state;
+    p.part_o = reinterpret_cast<float*>(ws + counter_bytes(l) + seq_state_bytes(l));
+    p.part_ml = p.part_o + rows * kHeadDim;
+
+    // The sequences' counters go to the device in pieces through a small host buffer: an asynchronous
+    // copy out of pageable memory has taken its source when the call returns.
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    constexpr int kPiece = 256;
+    int32_t piece[kPiece * 4];
+    for (int b0 = 0; b0 < l->batch; b0 += kPiece) {
+        const int nb = std::min(kPiece, l->batch - b0);
+        for (int i = 0; i < nb; ++i) {
+            const kivi_seq_state_t& x = st[b0 + i];
+            piece[4 * i + 0] = x.n_kq; piece[4 * i + 1] = x.n_kr;
+            piece[4 * i + 2] = x.k_r_start; piece[4 * i + 3] = x.v_r_start;
+        }
+        if (hipMemcpyAsync(dev_state + 4 * b0, piece, (size_t)nb * 4 * sizeof(int32_t), hipMemcpyHostToDevice, hs) != hipSuccess)
+            return KIVI_ERR_HIP;
+    }
+    p.rep_variant = rep_launch;
+    for (int h0 = 0; h0 < rep_total; h0 += kMaxRep) {
+        p.q_head0 = h0;
+        p.rep_here = std::min(kMaxRep, rep_total - h0);
+        const hipError_t e = launch_decode_mfma(p, hs);
+        if (e == hipErrorNotSupported) return KIVI_ERR_UNSUPPORTED;
+        if (int s2 = hip_status(e)) return s2;
+        p.k_new = p.v_new = nullptr;
+    }
+    return KIVI_OK;
+}
+
+// One decoding step of every sequence of a batch of different lengths in one pair of attention
+// launches (plus one flush launch per run of equal sequences that flush in this step, which is rare:
+// a sequence flushes every G-th step).  Served when every sequence's flush leaves the new token in
+// the window (then the flush can run out of the rings before the attention appends the token) and
+// the states after the step suit ragged_attention_fast.  Returns kNotApplicable with nothing launched
+// and nothing changed otherwise.
+int ragged_step_fast(const kivi_layout_t* l, const kivi_cache_t* c, kivi_seq_state_t* states, const void* k_new,
+                     const void* v_new, const void* q, float softmax_scale, int32_t policy, float* out,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (check_layout(l) != KIVI_OK || !c || !states) return kNotApplicable;        // the run-by-run path reports the error
+    if (policy != KIVI_FLUSH_WINDOW && policy != KIVI_FLUSH_ALG1) return kNotApplicable;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(q) || !aligned16(out) || !workspace || !aligned16(workspace))
+        return kNotApplicable;
+    if (decode_family(l) != KIVI_DECODE_MFMA || l->batch > 4096) return kNotApplicable;
+    // pass 1 (host only): every sequence's flush and its state after the step
+    kivi_seq_state_t after[4096];
+    int16_t nks[4096], nvs[4096];
+    for (int b = 0; b < l->batch; ++b) {
+        kivi_layout_t sl; kivi_cache_t sc;
+        if (kivi_batch_slice(l, c, b, 1, &states[b], &sl, &sc) != KIVI_OK) return kNotApplicable;
+        if (sc.n_kr >= l->cap_r_tokens || sc.n_vr >= l->cap_r_tokens) return kNotApplicable;
+        kivi_cache_t ap = sc;
+        ap.n_kr += 1; ap.n_vr += 1;
+        int nk = 0, nv = 0;
+        if (plan_flush(&sl, &ap, policy, &nk, &nv) != KIVI_OK) return kNotApplicable;
+        if (nk > sc.n_kr || nv > sc.n_vr || nk > 32767 || nv > 32767) return kNotApplicable;
+        nks[b] = (int16_t)nk; nvs[b] = (int16_t)nv;
+        after[b] = kivi_seq_state_t{sc.n_kq + nk, sc.n_vq + nv, (sc.k_r_start + nk) % l->cap_r_tokens, sc.n_kr - nk + 1,
+                                    (sc.v_r_start + nv) % l->cap_r_tokens, sc.n_vr - nv + 1};
+    }
+    // dry run of the attention's own conditions (no launch): the same checks it will make
+    {
+        const int rep_launch = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
+        const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
+        if (l->decode_path == KIVI_DECODE_MFMA_ONE || l->cap_q_tokens < kTileTokens) return kNotApplicable;
+        int max_tiles_a = 0, max_tiles_b = 0;
+        for (int b = 0; b < l->batch; ++b) {
+            const kivi_seq_state_t& x = after[b];
+            if (x.n_kq != x.n_vq || x.n_kr != x.n_vr || x.n_kr < 1 || x.n_kq % kTileTokens != 0) return kNotApplicable;
+            max_tiles_a = std::max(max_tiles_a, x.n_kq / kTileTokens);
+            max_tiles_b = std::max(max_tiles_b, ceil_div(x.n_kq + x.n_kr, kTileTokens) - x.n_kq / kTileTokens);
+        }
+        if (max_tiles_a < 1 || !residual_rows_possible(max_tiles_b, rep_variant)) return kNotApplicable;
+        const size_t rows = (size_t)l->batch * l->n_q_heads * (ceil_div(max_tiles_a, mfma_geometry(l->bits, rep_launch).chunk_tiles) + 1);
+        if (counter_bytes(l) + seq_state_bytes(l) + rows * (kHeadDim + 2) * sizeof(float) > workspace_bytes) return KIVI_ERR_WORKSPACE;
+    }
+    // pass 2: the flushes, one launch per run of consecutive sequences with equal state that flush
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    for (int b0 = 0; b0 < l->batch;) {
+        int b1 = b0 + 1;
+        while (b1 < l->batch && same_state(states[b0], states[b1])) ++b1;
+        if (nks[b0] > 0 || nvs[b0] > 0) {
+            kivi_layout_t sl; kivi_cache_t sc;
+            if (int s = kivi_batch_slice(l, c, b0, b1 - b0, &states[b0], &sl, &sc)) return s;
+            if (int s = enqueue_flush(&sl, &sc, nks[b0], nvs[b0], hs)) return s;
+        }
+        b0 = b1;
+    }
+    if (int s = ragged_attention_fast(l, c, after, q, softmax_scale, out, workspace, workspace_bytes, k_new, v_new, stream))
+        return s == kNotApplicable ? KIVI_ERR_UNSUPPORTED : s;       // cannot happen after the dry run
+    for (int b = 0; b < l->batch; ++b) states[b] = after[b];
+    return KIVI_OK;
+}
+
+}  // namespace
+
 // ---- kivi_decode_attention_static: the attention workspace as an array inside the library ----
 // For callers that cannot allocate.  Every device the library runs on holds its own copy of the
 // array at its own address; in host code the array's name is only a handle for
@@ -454,7 +620,7 @@ int kivi_decode_workspace_bytes(const kivi_layout_t* l, size_t* bytes) {
     if (int st = check_layout(l)) return st;
     if (!bytes) return KIVI_ERR_INVALID_ARG;
     const size_t rows = (size_t)l->batch * l->n_q_heads * max_splits(l);
-    *bytes = counter_bytes(l) + rows * (kHeadDim + 2) * sizeof(float);
+    *bytes = counter_bytes(l) + seq_state_bytes(l) + rows * (kHeadDim + 2) * sizeof(float);
     return KIVI_OK;
 }
 
@@ -667,6 +833,9 @@ int kivi_decode_step_ragged(const kivi_layout_t* l, const kivi_cache_t* c, kivi_
                             const void* k_new, const void* v_new, const void* q, float softmax_scale,
                             int32_t policy, float* out, void* workspace, size_t workspace_bytes, void* stream) {
     if (!k_new || !v_new || !q || !out) return KIVI_ERR_INVALID_ARG;
+    if (int s = ragged_step_fast(l, c, states, k_new, v_new, q, softmax_scale, policy, out, workspace, workspace_bytes, stream);
+        s != kNotApplicable)
+        return s;
     return for_each_run(l, c, states, true, [&](kivi_layout_t& sl, kivi_cache_t& sc, int b0) {
         const size_t kv_row = (size_t)l->n_kv_heads * kHeadDim, q_row = (size_t)l->n_q_heads * kHeadDim;
         return kivi_decode_step(&sl, &sc, static_cast<const __half*>(k_new) + b0 * kv_row,
@@ -676,10 +845,63 @@ int kivi_decode_step_ragged(const kivi_layout_t* l, const kivi_cache_t* c, kivi_
     });
 }
 
+int kivi_decode_launches_ragged(const kivi_layout_t* l, const kivi_seq_state_t* states, int32_t* launches) {
+    if (int s = check_layout(l)) return s;
+    if (!states || !launches) return KIVI_ERR_INVALID_ARG;
+    const int path = decode_family(l);
+    const int rep_total = l->n_q_heads / l->n_kv_heads;
+    const int head_groups = ceil_div(rep_total, kMaxRep);
+    // the conditions of ragged_attention_fast
+    bool fast = path == KIVI_DECODE_MFMA && l->decode_path != KIVI_DECODE_MFMA_ONE && l->cap_q_tokens >= kTileTokens;
+    int max_tiles_a = 0, max_tiles_b = 0;
+    for (int b = 0; b < l->batch; ++b) {
+        const kivi_seq_state_t& x = states[b];
+        if (x.n_kq < 0 || x.n_vq < 0 || x.n_kr < 0 || x.n_vr < 0 || x.n_kq + x.n_kr != x.n_vq + x.n_vr) return KIVI_ERR_INVALID_ARG;
+        if (x.n_kq != x.n_vq || x.n_kr < 1 || x.n_kq % kTileTokens != 0) fast = false;
+        max_tiles_a = std::max(max_tiles_a, x.n_kq / kTileTokens);
+        max_tiles_b = std::max(max_tiles_b, ceil_div(x.n_kq + x.n_kr, kTileTokens) - x.n_kq / kTileTokens);
+    }
+    const int rep_launch = std::min(rep_total, kMaxRep);
+    if (fast && max_tiles_a >= 1 && residual_rows_possible(max_tiles_b, rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8))) {
+        *launches = 2 * head_groups;
+        return KIVI_OK;
+    }
+    // run by run
+    int total = 0;
+    for (int b0 = 0; b0 < l->batch;) {
+        int b1 = b0 + 1;
+        while (b1 < l->batch && same_state(states[b0], states[b1])) ++b1;
+        const kivi_seq_state_t& x = states[b0];
+        if (x.n_kq + x.n_kr > 0) {
+            kivi_layout_t sl = *l;
+            sl.batch = b1 - b0;
+            kivi_cache_t sc{};
+            sc.n_kq = x.n_kq; sc.n_vq = x.n_vq; sc.n_kr = x.n_kr; sc.n_vr = x.n_vr;
+            const bool two = wants_two_launches(&sl, &sc, path);
+            const bool split = head_split_shift(&sl, plan_splits(&sl, &sc, path == KIVI_DECODE_MFMA, two), path, two) > 0;
+            total += path == KIVI_DECODE_MFMA ? (split ? 1 : head_groups * (two ? 2 : 1)) : head_groups + 1;
+        }
+        b0 = b1;
+    }
+    *launches = total;
+    return KIVI_OK;
+}
+
 int kivi_decode_attention_ragged(const kivi_layout_t* l, const kivi_cache_t* c, const kivi_seq_state_t* states,
                                  const void* q, float softmax_scale, float* out, void* workspace,
                                  size_t workspace_bytes, void* stream) {
     if (!q || !out) return KIVI_ERR_INVALID_ARG;
+    if (check_layout(l) == KIVI_OK && c && states && aligned16(q) && aligned16(out) && workspace && aligned16(workspace)) {
+        bool ok = true;
+        for (int b = 0; b < l->batch && ok; ++b) {
+            kivi_layout_t sl; kivi_cache_t sc;
+            ok = kivi_batch_slice(l, c, b, 1, &states[b], &sl, &sc) == KIVI_OK;     // validates the sequence's counters
+        }
+        if (ok) {
+            const int s = ragged_attention_fast(l, c, states, q, softmax_scale, out, workspace, workspace_bytes, nullptr, nullptr, stream);
+            if (s != kNotApplicable) return s;
+        }
+    }
     return for_each_run(l, c, const_cast<kivi_seq_state_t*>(states), false,
                         [&](kivi_layout_t& sl, kivi_cache_t& sc, int b0) {
         if (sc.n_kq + sc.n_kr == 0 && sc.n_vq + sc.n_vr == 0) return (int)KIVI_OK;      // empty slots of the batch

@@ -50,8 +50,17 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxSlots = kMfmaSplitTiles / 4;          // most tile slots per wavefront (4)
 constexpr int kWaveTokens = kMaxSlots * kTileTokens;    // 128: token slots of a wavefront's LDS rows
+// Floats per row of the logit / probability rows: the lanes that hold the matrix columns of one
+// row-quad write 16 bytes each at the same offset of their rows, so the row stride must not be a
+// multiple of 32 dwords (8-way conflicts with 4 heads per kv-head: 45.6 -> 44.1 us there).
+constexpr int kLrRow = kWaveTokens + 4;
 constexpr int kKRow = 136;   // halves per column of the key-side B staging (272 B: bank skew)
 constexpr int kVRow = 40;    // halves per column of the value-side B staging (80 B: bank skew)
+// Extra halves between the columns of consecutive channel groups: the even and the odd lanes of a
+// wavefront write the operands of channel groups two apart in one instruction, and without the skew
+// those land on the same banks whenever (matrix columns x kVRow / 2) is a multiple of 32 dwords
+// (4 query heads per kv-head: 47.3 -> 45.5 us at the Mistral-shaped configuration).
+constexpr int kVSkew = 16;
 constexpr float kUnscale = 16777216.0f;                 // 2^24: codes enter as code * 2^-24
 constexpr float kDownscale = 1.0f / 16777216.0f;
 
@@ -180,9 +189,9 @@ struct WaveLds {
     static constexpr int NC = 2 * REP;
     static constexpr int kStageSlots = SS;              // tile slots staged at once
     static constexpr int kKSlot = NC * kKRow;          // halves per staged key-side operand
-    static constexpr int kVSlot = 4 * NC * kVRow;      // halves per staged value-side operand
+    static constexpr int kVSlot = 4 * NC * kVRow + 3 * kVSkew;      // halves per staged value-side operand
     static constexpr int kBHalves = kStageSlots * (kKSlot > kVSlot ? kKSlot : kVSlot);
-    __align__(16) float lr[NC][kWaveTokens];
+    __align__(16) float lr[NC][kLrRow];
     __align__(16) __half b[kBHalves];
     __align__(16) float zt[NC][kMaxSlots];
 };
@@ -203,7 +212,7 @@ __device__ __forceinline__ void stage_key_operand(__half* bw, __half2 s2, const 
 
 // Raw logits of one quantised key tile: D = codes x operand; column n of D goes to lr[n][slot*32 + token].
 template <int BITS, int REP>
-__device__ __forceinline__ void key_tile_mfma(const uint32_t* w, const __half* bw, float (*lr)[kWaveTokens],
+__device__ __forceinline__ void key_tile_mfma(const uint32_t* w, const __half* bw, float (*lr)[kLrRow],
                                               int slot, int lane) {
     constexpr int NC = 2 * REP;
     const int n = lane & 15, rq = lane >> 4, ncol = n & (NC - 1);
@@ -229,7 +238,7 @@ __device__ __forceinline__ void key_tile_mfma(const uint32_t* w, const __half* b
 // the softmax has set their probabilities to 0 and their (re-read) scales are finite.
 template <int BITS, int REP, bool MASKED>
 __device__ __forceinline__ void stage_value_operand(__half* bw, __half2 s2, __half2 z2, int n_valid,
-                                                    const float (*lr)[kWaveTokens], int slot,
+                                                    const float (*lr)[kLrRow], int slot,
                                                     float (&zacc)[REP][2], int lane) {
     constexpr int NC = 2 * REP;
     const int t = lane >> 1, cg0 = (lane & 1) * 2;
@@ -243,10 +252,10 @@ __device__ __forceinline__ void stage_value_operand(__half* bw, __half2 s2, __ha
         __half h0, l0, h1, l1;
         split_hi_lo(pt * s0, h0, l0);
         split_hi_lo(pt * s1, h1, l1);
-        bw[((cg0 + 0) * NC + 2 * hh) * kVRow + t] = h0;
-        bw[((cg0 + 0) * NC + 2 * hh + 1) * kVRow + t] = l0;
-        bw[((cg0 + 1) * NC + 2 * hh) * kVRow + t] = h1;
-        bw[((cg0 + 1) * NC + 2 * hh + 1) * kVRow + t] = l1;
+        bw[((cg0 + 0) * NC + 2 * hh) * kVRow + (cg0 + 0) * kVSkew + t] = h0;
+        bw[((cg0 + 0) * NC + 2 * hh + 1) * kVRow + (cg0 + 0) * kVSkew + t] = l0;
+        bw[((cg0 + 1) * NC + 2 * hh) * kVRow + (cg0 + 1) * kVSkew + t] = h1;
+        bw[((cg0 + 1) * NC + 2 * hh + 1) * kVRow + (cg0 + 1) * kVSkew + t] = l1;
         zacc[hh][0] = fmaf(pt, z0, zacc[hh][0]);
         zacc[hh][1] = fmaf(pt, z1, zacc[hh][1]);
     }
@@ -259,7 +268,7 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
     half8 bf[4];
 #pragma unroll
     for (int cg = 0; cg < 4; ++cg)
-        bf[cg] = *reinterpret_cast<const half8*>(bw + (cg * NC + ncol) * kVRow + rq * 8);
+        bf[cg] = *reinterpret_cast<const half8*>(bw + (cg * NC + ncol) * kVRow + cg * kVSkew + rq * 8);
 #pragma unroll
     for (int u = 0; u < 8; ++u)
         acc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_fragment<BITS>(w, u >> 1, u & 1), bf[u >> 1],
@@ -273,10 +282,14 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
 // many wavefronts per compute unit, one part per tile in the workspace) and this kernel follows as
 // kQuantisedOnly: the all-quantised chunks only; whoever finishes a unit merges the parts of the
 // first launch into it.
-constexpr int kBothPhases = 0, kQuantisedOnly = 1;
+// kQuantisedRagged: kQuantisedOnly over a batch whose sequences differ in length (every unit's own
+// number of all-quantised tiles from p.seq_state); an instantiation of its own so that batches of
+// one length pay nothing for it.
+constexpr int kBothPhases = 0, kQuantisedOnly = 1, kQuantisedRagged = 2;
 
 template <int BITS, int REP, int SLOTS, int OCC, int MODE, int HSHIFT = 0>
 __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
+    constexpr bool kQOnly = MODE != kBothPhases, kRagged = MODE == kQuantisedRagged;
     constexpr int kSlots = SLOTS;
     // tile slots staged at once: two where that divides the slots and the registers allow
     constexpr int kStage = REP > 2 ? 1 : (SLOTS % 2 == 0 ? 2 : SLOTS);
@@ -323,7 +336,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     };
     auto batch_of = [&](int u) -> int { return kv_unit(u) / p.n_kv_heads; };
     // chunks per unit on this launch's cost axis: all-quantised / with fp16 rows
-    const int n_a = p.plan.n_splits_a, n_b = MODE == kQuantisedOnly ? 0 : p.plan.n_splits_b;
+    const int n_a = p.plan.n_splits_a, n_b = kQOnly ? 0 : p.plan.n_splits_b;
     const int cpu = p.plan.n_splits_a + p.plan.n_splits_b;       // workspace rows per (batch, query head)
     // this workgroup's ranges in the two global chunk index spaces (unit-major)
     // Index arithmetic on the cost axis; 32-bit whenever the products fit (64-bit division costs
@@ -362,6 +375,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // per-unit stride is.
     int nx_u = 0, nx_j = 0, nx_nt = 1;
     int nx_lo = 0, nx_len = 1, nx_rot = 0;     // this workgroup's chunk range in unit nx_u, rotation
+    int nx_tiles_a = p.plan.tiles_a;           // all-quantised tiles of unit nx_u
     bool nx_ok = false;
     int64_t nx_base = 0;
     auto set_next = [&](int ck, bool first_call) {
@@ -379,20 +393,31 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             nx_lo = max(first_a - nx_u * n_a, 0);
             nx_len = max(min(last_a - nx_u * n_a, n_a) - nx_lo, 1);
             nx_rot = (nx_u * 3) % nx_len;
+            if constexpr (kRagged) {
+                // a batch of different lengths: the unit's own number of all-quantised tiles (the plan
+                // holds the longest sequence's; a shorter one's surplus chunks come out empty)
+                nx_tiles_a = nx_ok ? p.seq_state[4 * batch_of(nx_u)] / kTileTokens : p.plan.tiles_a;
+            }
         }
         int j_phys = nx_j + nx_rot;                          // nx_j runs over [nx_lo, nx_lo + nx_len)
         j_phys -= j_phys >= nx_lo + nx_len ? nx_len : 0;
         const int tile0 = j_phys * p.plan.tiles_per_split_a;
-        nx_nt = min(p.plan.tiles_per_split_a, p.plan.tiles_a - tile0);
+        nx_nt = min(p.plan.tiles_per_split_a, nx_tiles_a - tile0);
         nx_base = (int64_t)kv_unit(nx_u) * p.cap_tiles + tile0;
+        if constexpr (kRagged) {
+            if (nx_nt <= 0) nx_base -= tile0;                // an empty chunk: its (masked) slots re-read the unit's tile 0
+        }
     };
-    auto chunk_tile = [&](int slot_or_row) -> int64_t { return nx_base + min(wave + 4 * slot_or_row, nx_nt - 1); };
+    auto chunk_tile = [&](int slot_or_row) -> int64_t {
+        const int t = min(wave + 4 * slot_or_row, nx_nt - 1);
+        return nx_base + (kRagged ? max(t, 0) : t);
+    };
     // Requests for the "next" all-quantised chunk.  They are issued unconditionally so that the
     // compiler can count outstanding loads exactly (a conditional load forces a wait for *all*
     // outstanding loads at the next use); when there is no next chunk they read tile 0 of unit 0,
     // which stays in L2, and the result is never used.
     auto request_zero_rows = [&]() {
-        const int64_t tile = nx_ok ? nx_base + min(wave + 4 * min(n, kSlots - 1), nx_nt - 1) : 0;   // A row n = slot n
+        const int64_t tile = nx_ok ? chunk_tile(min(n, kSlots - 1)) : 0;   // A row n = slot n
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
             zf[ks] = *reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8);
@@ -432,7 +457,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         len_b = n_b ? owner(base + (n_b - 1) * cost_b) - gb0 + 1 : 0;
         ga0 = n_a ? owner(a0) : 0;
         len_a = n_a ? owner(a0 + n_a - 1) - ga0 + 1 : 0;
-        if (MODE == kQuantisedOnly) {       // the parts the fp16-row launch left for the unit: one per tile
+        if (kQOnly) {       // the parts the fp16-row launch left for the unit: one per tile
             gb0 = 0;
             len_b = p.plan.n_splits_b;
         }
@@ -449,7 +474,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // while the workgroup merges, writes the output and stages the next query.  (kBothPhases keeps
     // __syncthreads(): its launches have one unit per workgroup where this would matter.)
     auto unit_barrier = [&]() {
-        if constexpr (MODE == kQuantisedOnly) lds_barrier();
+        if constexpr (kQOnly) lds_barrier();
         else __syncthreads();
     };
     __half q_pre[kIdx];
@@ -515,9 +540,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         // kQuantisedOnly: the only workgroup of a unit's all-quantised range merges the first launch's
         // parts into its own and writes the output; otherwise the counter runs over the workgroups of
         // this launch and the last one merges all parts.
-        const bool merge_rows_parts = MODE == kQuantisedOnly && len_a == 1 && len_b > 0;
+        const bool merge_rows_parts = kQOnly && len_a == 1 && len_b > 0;
         const int n_parts = (sole || hold_put >= 0 || hold_get >= 0 || merge_rows_parts) ? 1 : len_a + len_b;
-        const int n_counted = MODE == kQuantisedOnly ? len_a : n_parts;
+        const int n_counted = kQOnly ? len_a : n_parts;
         const int part = fp16_phase ? g - gb0 : len_b + g - ga0;
         const int row_stride = cpu;                               // workspace rows per (batch, query head)
         // one output element (query head hh, channel c); p0_*: part 0 of the fp16-row launch (kQuantisedOnly)
@@ -597,7 +622,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                 }
             }
         };
-        if constexpr (MODE == kQuantisedOnly && kPrefetchPart) {
+        if constexpr (kQOnly && kPrefetchPart) {
 #pragma unroll
             for (int k = 0; k < kIdx; ++k)
                 if (tid + 256 * k < rep * kHeadDim) finish_element(tid + 256 * k, pre_m[k], pre_l[k], pre_o[k]);
@@ -683,7 +708,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             sm_qf[2 * hh][c] = hi;
             sm_qf[2 * hh + 1][c] = lo;
         };
-        if constexpr (MODE == kQuantisedOnly) {
+        if constexpr (kQOnly) {
 #pragma unroll
             for (int k = 0; k < kIdx; ++k) {           // the query was requested one unit ahead
                 const int i = tid + 256 * k;
@@ -787,7 +812,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     };
     const int ub_lo = first_b < last_b ? first_b / max(n_b, 1) : 0;
     const int ub_hi = first_b < last_b ? (last_b - 1) / max(n_b, 1) : -1;
-    if constexpr (MODE != kQuantisedOnly) {
+    if constexpr (!kQOnly) {
     for (int u = ub_lo; u <= ub_hi; ++u) {
         const int b_lo = max(first_b, u * n_b), b_hi = min(last_b, (u + 1) * n_b);
         if (u > ub_lo) finish_fp16_unit(u - 1);
@@ -988,7 +1013,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // ================= phase 2: this workgroup's all-quantised chunks =================
     // Software-pipelined across chunk and unit borders: the next chunk's data is requested while
     // the current one is consumed.
-    if constexpr (MODE == kQuantisedOnly) {         // the first query ahead of the first chunk: loads return in order
+    if constexpr (kQOnly) {         // the first query ahead of the first chunk: loads return in order
         if (first_a < last_a) request_q(first_a / n_a);
     }
     if constexpr (!kEarlyKeys) initial_request_keys();
@@ -1008,13 +1033,26 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     for (int u = ua_lo; u <= ua_hi; ++u) {
         const int a_lo = max(first_a, u * n_a), a_hi = min(last_a, (u + 1) * n_a);
         const bool carried = carry && u == ua_lo;
-        if (MODE == kQuantisedOnly && kPrefetchPart) request_rows_part(u);
+        if (kQOnly && kPrefetchPart) request_rows_part(u);
         if (!carried) enter_unit(u);
-        if (MODE == kQuantisedOnly && u < ua_hi) request_q(u + 1);
+        if (kQOnly && u < ua_hi) request_q(u + 1);
         for (int ck = a_lo; ck < a_hi; ++ck) {
             const int n_tiles = nx_nt;                   // the chunk requested last is the one processed now
             set_next(ck + 1, false);
             const int cnt = n_tiles > wave ? (n_tiles - wave + 3) / 4 : 0;     // valid slots of this wavefront
+            if constexpr (kRagged) {
+                // A batch of different lengths: a chunk past the end of a shorter sequence is empty.  Its
+                // data (a re-read tile that may never have been written) is dropped unseen; only the
+                // requests for the chunk after it are made, in the usual order.
+                if (n_tiles <= 0) {
+                    request_zero_rows();
+#pragma unroll
+                    for (int i = 0; i < kSlots; ++i) request_key_slot(i);
+#pragma unroll
+                    for (int i = 0; i < kSlots; ++i) request_value_slot(i);
+                    continue;
+                }
+            }
             // key z-terms of the wave's four slots: one 16x16x128 product
             {
                 float4v d = {0.f, 0.f, 0.f, 0.f};
@@ -1138,8 +1176,13 @@ hipError_t launch_two(DecodeParams p, hipStream_t stream) {
     p.cost_b = 1;
     p.cost_unit = p.plan.n_splits_a;
     p.total_cost = total_a;
-    const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedOnly>(), total_a);
-    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedOnly><<<grid, 256, 0, stream>>>(p);
+    if (p.seq_state) {
+        const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedRagged>(), total_a);
+        decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedRagged><<<grid, 256, 0, stream>>>(p);
+    } else {
+        const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedOnly>(), total_a);
+        decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedOnly><<<grid, 256, 0, stream>>>(p);
+    }
     return hipGetLastError();
 }
 

@@ -106,6 +106,11 @@ struct DecodeParams {
     // > 0: the matrix-core family runs as two launches (fp16 rows, then the all-quantised chunks); the
     // plan then has a single fp16-row split per unit (n_splits_b == 1).
     int32_t two_launches;
+    // Batches whose sequences differ in length (two-launch form only; null otherwise): per batch entry
+    // {n_q, n_r, k_r_start, v_r_start} in device memory (K and V split alike).  The scalar counters
+    // and the plan above then describe the LONGEST sequence: every unit gets that many chunks on the
+    // cost axis, and a shorter sequence's surplus chunks and tiles are masked.
+    const int32_t* seq_state;
     // Host side only (two-launch form): the residual flush of this decode step, to be carried out by
     // extra workgroups of the fp16-row launch instead of a launch of its own; null otherwise.
     const QuantKeyParams* flush_k;

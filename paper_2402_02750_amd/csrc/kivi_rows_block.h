@@ -72,19 +72,25 @@ __device__ __forceinline__ void residual_rows_block(const DecodeParams& p, float
     float (*sm_p)[kTileTokens] = reinterpret_cast<float (*)[kTileTokens]>(sm_dyn) + wave * REP;   // [REP][32] of this wavefront
     float* sm_part = sm_dyn + tiles_b * REP * kTileTokens;                                          // [tiles_b][REP][130]
     const int64_t unit = unit_index;
-    const int tt = (p.plan.tiles_a + wave) * kTileTokens;  // first token of the tile
     const int b = (int)(unit / p.n_kv_heads), h = (int)(unit % p.n_kv_heads);
+    // the sequence's counters: the launch's, or (batches of different lengths) its entry of seq_state
+    int n_q = p.n_kq, length = p.length, k_start = p.k_r_start, v_start = p.v_r_start;
+    if (p.seq_state) {
+        const int4 st = reinterpret_cast<const int4*>(p.seq_state)[b];      // n_q, n_r, k_r_start, v_r_start
+        n_q = st.x; length = st.x + st.y; k_start = st.z; v_start = st.w;
+    }
+    const int tt = (n_q / kTileTokens + wave) * kTileTokens;  // first token of the tile (past the end for a shorter sequence's surplus wavefronts)
     const int rep = p.rep_here, rep_total = p.n_q_heads / p.n_kv_heads;
     const int64_t q_row0 = (int64_t)b * p.n_q_heads + (int64_t)h * rep_total + p.q_head0;
     const bool fused_append = p.k_new != nullptr;
-    const int last = p.length - 1;
+    const int last = length - 1;
 
     // the key rows of the tile are requested up front: 8 rows per lane
     half8 kr[8], vr[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int t = min(tt + j * 4 + row, last);         // rows past the end re-read the last row (unused)
-        const __half* ks = p.k_resid + (unit * p.cap_r + ring_slot(p.k_r_start, t - p.n_kq, p.cap_r)) * kHeadDim;
+        const __half* ks = p.k_resid + (unit * p.cap_r + ring_slot(k_start, t - n_q, p.cap_r)) * kHeadDim;
         if (fused_append && t == last) ks = p.k_new + unit * kHeadDim;     // the newest token is not in the rings yet
         kr[j] = *reinterpret_cast<const half8*>(ks + seg * 8);
     }
@@ -95,7 +101,7 @@ __device__ __forceinline__ void residual_rows_block(const DecodeParams& p, float
     __half* new_dst = nullptr;
     if (owns_new) {
         const bool is_v = lane >= 16;
-        const int slot = is_v ? ring_slot(p.v_r_start, last - p.n_vq, p.cap_r) : ring_slot(p.k_r_start, last - p.n_kq, p.cap_r);
+        const int slot = is_v ? ring_slot(v_start, last - n_q, p.cap_r) : ring_slot(k_start, last - n_q, p.cap_r);
         new_row = *reinterpret_cast<const uint4*>((is_v ? p.v_new : p.k_new) + unit * kHeadDim + (lane & 15) * 8);
         new_dst = const_cast<__half*>(is_v ? p.v_resid : p.k_resid) + (unit * p.cap_r + slot) * kHeadDim + (lane & 15) * 8;
     }
@@ -120,7 +126,7 @@ __device__ __forceinline__ void residual_rows_block(const DecodeParams& p, float
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int t = min(tt + j * 4 + row, last);
-        const __half* vs = p.v_resid + (unit * p.cap_r + ring_slot(p.v_r_start, t - p.n_vq, p.cap_r)) * kHeadDim;
+        const __half* vs = p.v_resid + (unit * p.cap_r + ring_slot(v_start, t - n_q, p.cap_r)) * kHeadDim;
         if (fused_append && t == last) vs = p.v_new + unit * kHeadDim;
         vr[j] = *reinterpret_cast<const half8*>(vs + seg * 8);
     }
@@ -129,8 +135,8 @@ __device__ __forceinline__ void residual_rows_block(const DecodeParams& p, float
 #pragma unroll
     for (int hh = 0; hh < REP; ++hh) {
         const float a = lane < kTileTokens ? sm_p[hh][lane] : -INFINITY;
-        m[hh] = wave_max32(a);                             // finite: the tile holds at least one token
-        const float pt = lane < kTileTokens ? __expf(a - m[hh]) : 0.f;
+        m[hh] = wave_max32(a);                             // -inf only for a tile past the end of a shorter sequence
+        const float pt = lane < kTileTokens ? __expf(a - (m[hh] == -INFINITY ? 0.f : m[hh])) : 0.f;
         l[hh] = wave_sum32(pt);
         if (lane < kTileTokens) sm_p[hh][lane] = pt;
     }

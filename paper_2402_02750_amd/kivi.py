@@ -30,7 +30,7 @@ EXPORTS = [
     "kivi_quantize_key_groups", "kivi_quantize_value_tokens", "kivi_prefill", "kivi_append_residual",
     "kivi_flush_residual", "kivi_decode_attention", "kivi_decode_step", "kivi_stream_read_probe",
     "kivi_batch_slice", "kivi_decode_step_ragged", "kivi_decode_attention_ragged",
-    "kivi_decode_attention_static",
+    "kivi_decode_attention_static", "kivi_decode_launches_ragged",
 ]
 KIVI_STATIC_WORKSPACE_BYTES = 8 << 20
 
@@ -95,6 +95,7 @@ def load_library() -> ctypes.CDLL:
     lib.kivi_flush_residual.argtypes = [P(kivi_layout_t), P(kivi_cache_t), I32, P(I32), P(I32), VP]
     lib.kivi_decode_attention.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, ctypes.c_float,
                                           VP, VP, ctypes.c_size_t, VP]
+    lib.kivi_decode_launches_ragged.argtypes = [P(kivi_layout_t), P(kivi_seq_state_t), P(I32)]
     lib.kivi_decode_attention_static.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, ctypes.c_float, VP, VP]
     lib.kivi_decode_step.argtypes = [P(kivi_layout_t), P(kivi_cache_t), VP, VP, VP, ctypes.c_float, I32,
                                      VP, VP, ctypes.c_size_t, VP]
@@ -324,6 +325,14 @@ def kivi_decode_step_ragged(layout, cache: Cache, states, k_new, v_new, q_fp16, 
         policy, ctypes.c_void_p(out_fp32.data_ptr()), ctypes.c_void_p(cache.workspace.data_ptr()),
         cache.workspace.numel(), _stream_handle(stream)), "kivi_decode_step_ragged")
     return out_fp32
+
+
+def kivi_decode_launches_ragged(layout, states) -> int:
+    """Kernel launches kivi_decode_attention_ragged would enqueue for these sequence states."""
+    n = ctypes.c_int32(0)
+    _check(load_library().kivi_decode_launches_ragged(ctypes.byref(layout), states, ctypes.byref(n)),
+           "kivi_decode_launches_ragged")
+    return n.value
 
 
 def kivi_decode_attention_ragged(layout, cache: Cache, states, q_fp16, softmax_scale, out_fp32, stream=None):

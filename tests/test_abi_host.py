@@ -269,3 +269,29 @@ def test_decode_plan(lib):
     l = _layout()
     assert lib.kivi_decode_plan(ctypes.byref(l), None, ctypes.byref(bad)) == kivi.KIVI_ERR_INVALID_ARG
     assert lib.kivi_decode_plan(ctypes.byref(l), ctypes.byref(_fake_cache()), None) == kivi.KIVI_ERR_INVALID_ARG
+
+
+def test_decode_launches_ragged(lib):
+    """kivi_decode_launches_ragged: a batch of different lengths goes through one pair of launches when
+    every sequence splits K and V alike and has fp16 rows; run by run otherwise."""
+    l = kivi.make_layout(4, 8, 2, 2, 128, 4096, 192)
+    st = kivi.make_states(4)
+    for b, (nq, nr) in enumerate([(0, 50), (992, 130), (2048, 159), (64, 128)]):
+        st[b] = kivi.kivi_seq_state_t(nq, nq, 0, nr, 0, nr)
+    assert kivi.kivi_decode_launches_ragged(l, st) == 2
+    # 16 query heads per kv-head: two groups of 8, a pair of launches each
+    l16 = kivi.make_layout(4, 32, 2, 2, 128, 4096, 192)
+    assert kivi.kivi_decode_launches_ragged(l16, st) == 4
+    # an empty slot, or K and V split differently (Algorithm 1's policy): run by run
+    st[0] = kivi.kivi_seq_state_t()
+    assert kivi.kivi_decode_launches_ragged(l, st) >= 3
+    st[0] = kivi.kivi_seq_state_t(128, 100, 0, 10, 0, 38)
+    assert kivi.kivi_decode_launches_ragged(l, st) >= 4
+    # the vector-ALU family: decode + merge per run
+    lv = kivi.make_layout(4, 8, 2, 2, 128, 4096, 192, decode_path=kivi.KIVI_DECODE_VALU)
+    st[0] = kivi.kivi_seq_state_t(0, 0, 0, 50, 0, 50)
+    assert kivi.kivi_decode_launches_ragged(lv, st) == 8
+    bad = kivi.make_states(4)
+    bad[1] = kivi.kivi_seq_state_t(32, 0, 0, 5, 0, 5)
+    n = ctypes.c_int32(0)
+    assert lib.kivi_decode_launches_ragged(ctypes.byref(l), bad, ctypes.byref(n)) == kivi.KIVI_ERR_INVALID_ARG

@@ -71,6 +71,13 @@ def test_ragged_batch_steps(path, policy):
             gh.check_close(got[b:b + 1], oc.attention(q[b:b + 1], w.softmax_scale), f"step {step} seq {b}")
             if step % 16 == 15:
                 gh.compare_quantized_state(_SeqView(cache, b, st), oc)
+    # how the last step's attention was launched: one pair of launches for the whole batch where the
+    # matrix-core family serves a batch whose sequences all split K and V alike, run by run otherwise
+    launches = kivi.kivi_decode_launches_ragged(layout, states)
+    if policy == kivi.KIVI_FLUSH_WINDOW and path != kivi.KIVI_DECODE_VALU:
+        assert launches == 2
+    else:
+        assert launches >= 5
     # attention only, with one slot emptied: its rows of `out` stay as they are
     states[2] = kivi.kivi_seq_state_t()
     out.fill_(7.0)
@@ -81,3 +88,56 @@ def test_ragged_batch_steps(path, policy):
     assert (got[2] == 7.0).all()
     for b in (0, 1, 3, 4, 5):
         gh.check_close(got[b:b + 1], oracles[b].attention(q[b:b + 1], w.softmax_scale), f"final seq {b}")
+
+
+@pytest.mark.parametrize("bits,rep", [(2, 2), (4, 1), (2, 4)])
+def test_ragged_64_distinct_lengths(bits, rep):
+    """64 sequences, all of different lengths (from shorter than the residual window, nothing
+    quantised yet, to several chunks), decoded for 40 steps in one pair of attention launches per
+    step: every sequence against an oracle cache of its own, outputs at every 4th step and after every
+    flush, cache state at the end."""
+    torch = gh.require_gpu()
+    n_seq, steps = 64, 40
+    prompts = [20 + 41 * i for i in range(n_seq)]            # 20 ... 2603, all distinct
+    w = scaled(CONFIGS["stream"], name="ragged64", batch=n_seq, n_q_heads=2 * rep, n_kv_heads=2, bits=bits, residual=128,
+               prompt=0, decode_steps=0, seed=707 + bits)
+    total = max(prompts) + steps
+    k, v = workloads.keys(w, total), workloads.values(w, total)
+    layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, gh.round_up(total, 32), 192)
+    cache = kivi.Cache(layout)
+    states = kivi.make_states(w.batch)
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    oracles = []
+    print(f"case ragged64 bits={bits} rep={rep}: per-sequence prefill", flush=True)
+    for b, n in enumerate(prompts):
+        oc = ko.StreamingCache(1, w.n_kv_heads, 128, w.bits, w.group, w.residual, "window")
+        sl = kivi.CacheSlice(cache, b, 1)
+        kivi.kivi_prefill(sl.layout, kt[b:b + 1], vt[b:b + 1], n, sl, kivi.KIVI_FLUSH_WINDOW)
+        states[b] = sl.state()
+        oc.prefill(k[b:b + 1, :, :n], v[b:b + 1, :, :n])
+        oracles.append(oc)
+    out = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    lengths = list(prompts)
+    worst = 0.0
+    for step in range(steps):
+        q = workloads.queries(w, step)
+        k_new = torch.stack([kt[b, :, lengths[b]] for b in range(w.batch)]).contiguous()
+        v_new = torch.stack([vt[b, :, lengths[b]] for b in range(w.batch)]).contiguous()
+        before = [states[b].n_kq for b in range(w.batch)]
+        kivi.kivi_decode_step_ragged(layout, cache, states, k_new, v_new, torch.from_numpy(q).cuda(),
+                                     w.softmax_scale, out, kivi.KIVI_FLUSH_WINDOW)
+        torch.cuda.synchronize()
+        assert kivi.kivi_decode_launches_ragged(layout, states) == 2       # the whole batch in one pair of launches
+        got = out.cpu().numpy()
+        for b in range(w.batch):
+            oc = oracles[b]
+            oc.append(k[b:b + 1, :, lengths[b]], v[b:b + 1, :, lengths[b]])
+            lengths[b] += 1
+            st = states[b]
+            assert (st.n_kq, st.n_kr, st.n_vq, st.n_vr) == (oc.n_kq, oc.n_kr, oc.n_vq, oc.n_vr), f"step {step} seq {b}"
+            if step % 4 == 0 or st.n_kq != before[b] or step == steps - 1:
+                worst = max(worst, gh.check_close(got[b:b + 1], oc.attention(q[b:b + 1], w.softmax_scale), f"step {step} seq {b}"))
+        if step % 10 == 9:
+            print(f"case ragged64: step {step} ok, worst abs err {worst:.3e}", flush=True)
+    for b in range(w.batch):
+        gh.compare_quantized_state(_SeqView(cache, b, states[b]), oracles[b])
