@@ -145,13 +145,21 @@ __device__ __forceinline__ float inv_pos_factor(int j) {
     return BITS == 2 ? pow2_neg(2 * (j & 3)) : pow2_neg(4 * (j & 1));
 }
 
+// streaming (non-temporal) load of two fp16 numbers
+__device__ __forceinline__ __half2 nt_half2(const __half* p) {
+    union { uint32_t u; __half2 h; } r;
+    r.u = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+    return r.h;
+}
+
 template <int BITS>
 __device__ __forceinline__ void load_tile_words(const uint32_t* tile, int lane, uint32_t* w) {
     constexpr int kPlanes = BITS / 2;
 #pragma unroll
     for (int pl = 0; pl < kPlanes; ++pl) {
-        const uint4 v = *reinterpret_cast<const uint4*>(tile + pl * 256 + lane * 4);
-        w[pl * 4 + 0] = v.x; w[pl * 4 + 1] = v.y; w[pl * 4 + 2] = v.z; w[pl * 4 + 3] = v.w;
+        typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+        const uint4v v = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(tile + pl * 256 + lane * 4));
+        w[pl * 4 + 0] = v[0]; w[pl * 4 + 1] = v[1]; w[pl * 4 + 2] = v[2]; w[pl * 4 + 3] = v[3];
     }
 }
 
@@ -420,18 +428,18 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         const int64_t tile = nx_ok ? chunk_tile(min(n, kSlots - 1)) : 0;   // A row n = slot n
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            zf[ks] = *reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8);
+            zf[ks] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8));
     };
     auto request_key_slot = [&](int i) {
         const int64_t tile = nx_ok ? chunk_tile(i) : 0;
         load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
-        ks2[i] = *reinterpret_cast<const __half2*>(p.k_scale + tile * kHeadDim + 2 * lane);
+        ks2[i] = nt_half2(p.k_scale + tile * kHeadDim + 2 * lane);
     };
     auto request_value_slot = [&](int i) {
         const int64_t tile = nx_ok ? chunk_tile(i) : 0;
         load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
-        vs2[i] = *reinterpret_cast<const __half2*>(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
-        vz2[i] = *reinterpret_cast<const __half2*>(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+        vs2[i] = nt_half2(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
+        vz2[i] = nt_half2(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
     };
 
     // per-wave running state of the current unit

@@ -410,6 +410,336 @@ __device__ __forceinline__ void quantize_value_block(const QuantValueParams& p, 
     }
 }
 
+// ---- prefill forms: one wavefront per tile, everything in registers ----
+// The kernels above stage a tile in LDS and pass three barriers; at prefill sizes they are bound by
+// instruction issue (868 / 1022 vector instructions per tile for keys / values at 2 bits).  For
+// the bulk case -- a plain (non-ring) source, G = 32, whole tiles -- these forms give every wavefront
+// a tile of its own: the lanes load the elements whose codes they will pack, group minimum and
+// maximum come from packed fp16 min / max in registers plus at most two cross-lane steps, the
+// partial words of the lanes that share a word are combined with DPP moves, and nothing goes
+// through LDS.  Same arithmetic contract as above (encode_fast with the exact redo).
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+constexpr int kQuadXor1 = 0xB1, kQuadXor2 = 0x4E;      // quad_perm [1,0,3,2], [2,3,0,1]
+__device__ __forceinline__ uint32_t as_bits(half2v x) {
+    union { half2v h; uint32_t u; } a;
+    a.h = x;
+    return a.u;
+}
+__device__ __forceinline__ half2v as_half2(uint32_t x) {
+    union { half2v h; uint32_t u; } a;
+    a.u = x;
+    return a.h;
+}
+__device__ __forceinline__ float half_bits_to_float(uint32_t low16) { return (float)as_half2(low16).x; }
+// {a.x, b.x} and {a.y, b.y} (one byte-permute instruction each)
+__device__ __forceinline__ half2v low_halves(half2v a, half2v b) {
+    return as_half2(__builtin_amdgcn_perm(as_bits(b), as_bits(a), 0x05040100u));
+}
+__device__ __forceinline__ half2v high_halves(half2v a, half2v b) {
+    return as_half2(__builtin_amdgcn_perm(as_bits(b), as_bits(a), 0x07060302u));
+}
+template <int CTRL>
+__device__ __forceinline__ half2v dpp_h2(half2v x) {
+    union { half2v h; int i; } a, r;
+    a.h = x;
+    r.i = __builtin_amdgcn_mov_dpp(a.i, CTRL, 0xF, 0xF, true);
+    return r.h;
+}
+// A wavefront-uniform pointer pinned to scalar registers: keeps the compiler from folding a lane offset
+// into it early and then carrying every row address in vector registers (64-bit vector multiply-adds).
+typedef const half2v __attribute__((address_space(1)))* GlobalHalf2Ptr;       // keeps the loads global (not flat)
+__device__ __forceinline__ GlobalHalf2Ptr uniform_pointer(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<GlobalHalf2Ptr>(((uint64_t)hi << 32) | lo);
+}
+// mask ? a : b per bit (one bitfield-insert instruction)
+__device__ __forceinline__ uint32_t select_bits(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
+
+__device__ __forceinline__ float encode_fast16(_Float16 x, float y, float c0, float& dev) {
+    const float q = fmaf((float)x, y, c0);
+    const float r = __builtin_rintf(q);
+    dev = fmaxf(dev, fabsf(q - r));
+    return r;
+}
+
+// Keys: lane l holds channels 2l, 2l + 1 of all 32 tokens (each row load of the wavefront is one
+// contiguous 256-byte row).  A channel's group is the lane's own column: no cross-lane step for
+// minimum and maximum.  A word of the packed tile (tokens t0 and t0 + 16, 8 or 4 consecutive
+// channels) is shared by 4 (B = 2) or 2 (B = 4) neighbouring lanes.
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_keys_stream_kernel(QuantKeyParams p) {
+    const int lane = threadIdx.x & 63;
+    const int g = (int)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // group = tile
+    if (g >= p.n_tiles) return;                     // whole wavefronts leave; the kernel has no barrier
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int64_t unit = (int64_t)b * p.n_kv_heads + h;
+    constexpr float levels = (float)((1 << BITS) - 1);
+    // (the row address stays wavefront-uniform and the lane adds a 32-bit offset: scalar address arithmetic)
+    const __half* src = p.src.base + (int64_t)b * p.src.stride_b + (int64_t)h * p.src.stride_h
+                        + (int64_t)g * kTileTokens * p.src.stride_t;
+    half2v x[kTileTokens];
+#pragma unroll
+    for (int t = 0; t < kTileTokens; ++t)
+        x[t] = __builtin_nontemporal_load(uniform_pointer(src + t * p.src.stride_t) + (uint32_t)lane);
+
+    half2v mn[16], mx[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { mn[i] = pk_min(x[i], x[i + 16]); mx[i] = pk_max(x[i], x[i + 16]); }
+#pragma unroll
+    for (int w = 8; w >= 1; w >>= 1)
+#pragma unroll
+        for (int i = 0; i < w; ++i) { mn[i] = pk_min(mn[i], mn[i + w]); mx[i] = pk_max(mx[i], mx[i + w]); }
+
+    float y[2], c0[2], zf[2], sf[2], tol = 0.f;
+    half2v s2, z2;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const float lo = (float)mn[0][i], hi = (float)mx[0][i];
+        const _Float16 s16 = (_Float16)((hi - lo) / levels);          // fp32 division, rounded to nearest even
+        const GroupConst gc = group_const(lo, (float)s16);
+        y[i] = gc.y; c0[i] = gc.c0; zf[i] = gc.z; sf[i] = gc.s;
+        tol = fmaxf(tol, gc.tol);
+        s2[i] = s16;
+        z2[i] = mn[0][i];
+    }
+    const int dst_tile = p.first_tile + g;
+    const int64_t o = (unit * p.cap_tiles + dst_tile) * kHeadDim + 2 * lane;
+    *reinterpret_cast<half2v*>(p.scale + o) = s2;
+    *reinterpret_cast<half2v*>(p.zero + o) = z2;
+
+    constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
+    uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;
+    const int ks = lane >> 4, q = (lane >> 2) & 3, k = lane & 3;     // channel 2l = ks*32 + q*8 + 2k
+    const int shift = BITS == 2 ? 2 * k : 4 * (k & 1);
+    const uint32_t m0 = 0u - (uint32_t)(k & 1), m1 = 0u - (uint32_t)(k >> 1);
+    const float thr = 0.5f - tol;
+    // four tokens t0 (and their partners t0 + 16) at a time: byte i*2 + uo of the lane's partial word
+    // holds the code of (channel 2l + i, token t0 + 16 uo) -- bits (e&1)*16 + 8*uo of the layout --
+    // and the shift moves it to the lane's channel pair
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+        uint32_t pw[4];
+        float dev = 0.f;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const int t0 = blk * 4 + tt;
+            uint32_t w = 0;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int uo = 0; uo < 2; ++uo)
+                    w = __builtin_amdgcn_cvt_pk_u8_f32(encode_fast16(x[t0 + 16 * uo][i], y[i], c0[i], dev), i * 2 + uo, w);
+            pw[tt] = w;
+        }
+        if (dev > thr) {      // rare: a quotient next to a rounding tie; redo the lane's 16 codes with true divisions
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const int t0 = blk * 4 + tt;
+                uint32_t w = 0;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int uo = 0; uo < 2; ++uo)
+                        w |= encode((float)x[t0 + 16 * uo][i], zf[i], sf[i], levels) << (8 * (i * 2 + uo));
+                pw[tt] = w;
+            }
+        }
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) pw[tt] <<= shift;
+        // The lanes that share a word combine their partial words so that each ends up with a different
+        // token's complete word (a transpose over the lane group, 3 instructions per exchange): with the
+        // odd neighbour, the odd lane keeps the odd tokens and hands over the even ones, and vice versa;
+        // at 2 bits the same once more two lanes apart.
+        const uint32_t a = select_bits(m0, pw[1], pw[0]) | dpp_u32<kQuadXor1>(select_bits(m0, pw[0], pw[1]));   // token (k & 1)
+        const uint32_t c = select_bits(m0, pw[3], pw[2]) | dpp_u32<kQuadXor1>(select_bits(m0, pw[2], pw[3]));   // token 2 + (k & 1)
+        if (BITS == 2) {
+            const uint32_t w = select_bits(m1, c, a) | dpp_u32<kQuadXor2>(select_bits(m1, a, c));               // token k
+            dst[(q * 16 + blk * 4 + k) * 4 + ks] = w;
+        } else {
+            const int i = ks * 2 + (k >> 1);
+            dst[(i >> 2) * 256 + (q * 16 + blk * 4 + (k & 1)) * 4 + (i & 3)] = a;
+            dst[(i >> 2) * 256 + (q * 16 + blk * 4 + 2 + (k & 1)) * 4 + (i & 3)] = c;
+        }
+    }
+}
+
+// Values: lane (tl = l / 16, seg = l % 16) holds channels seg*8 .. seg*8 + 7 of tokens 8 tl .. 8 tl + 7
+// (a 16-byte load per token).  A group is 32 channels of a token = the 4 lanes of a quad; lane jj of
+// the quad derives the constants of tokens jj and jj + 4 and the others get them by quad broadcasts.
+// A word (8 tokens, channels c and c + 16) is shared by the lanes seg and seg ^ 2.
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_values_stream_kernel(QuantValueParams p) {
+    const int lane = threadIdx.x & 63;
+    const int ti = (int)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    if (ti >= p.n_tokens / kTileTokens) return;     // whole wavefronts leave; the kernel has no barrier
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int64_t unit = (int64_t)b * p.n_kv_heads + h;
+    constexpr float levels = (float)((1 << BITS) - 1);
+    const int dst_tile = p.first_token / kTileTokens + ti;
+    const int tl = lane >> 4, seg = lane & 15, g = seg >> 2, jj = seg & 3, odd = (seg >> 1) & 1;
+    const __half* src = p.src.base + (int64_t)b * p.src.stride_b + (int64_t)h * p.src.stride_h
+                        + ((int64_t)ti * kTileTokens + tl * 8) * p.src.stride_t + seg * 8;
+    typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+    union Row { uint4v v4; half2v h2[4]; _Float16 h[8]; } x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i].v4 = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(src + i * p.src.stride_t));
+
+    // Group minimum / maximum of every token.  In the lane: packed fp16 min / max over its 8 channels
+    // (exact, no arithmetic); the halves of two tokens are then combined into one register
+    // (token i in the low half, token i + 1 in the high half), so that the two exchanges inside the quad
+    // serve two tokens at once.  Lane jj adopts the tokens jj and jj + 4.
+    half2v pmn[4], pmx[4];
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+        half2v lo2[2], hi2[2];
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            lo2[d] = pk_min(pk_min(x[i + d].h2[0], x[i + d].h2[1]), pk_min(x[i + d].h2[2], x[i + d].h2[3]));
+            hi2[d] = pk_max(pk_max(x[i + d].h2[0], x[i + d].h2[1]), pk_max(x[i + d].h2[2], x[i + d].h2[3]));
+        }
+        half2v mn = pk_min(low_halves(lo2[0], lo2[1]), high_halves(lo2[0], lo2[1]));
+        half2v mx = pk_max(low_halves(hi2[0], hi2[1]), high_halves(hi2[0], hi2[1]));
+        mn = pk_min(mn, dpp_h2<kQuadXor1>(mn)); mx = pk_max(mx, dpp_h2<kQuadXor1>(mx));
+        mn = pk_min(mn, dpp_h2<kQuadXor2>(mn)); mx = pk_max(mx, dpp_h2<kQuadXor2>(mx));
+        pmn[i >> 1] = mn;
+        pmx[i >> 1] = mx;
+    }
+    float my_lo[2], my_hi[2];
+    {
+        const uint32_t upper = 0u - (uint32_t)(jj >> 1);     // tokens 2, 3 (6, 7) are in the second register of a slot
+        const int sh = 16 * (jj & 1);
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            my_lo[sl] = half_bits_to_float(select_bits(upper, as_bits(pmn[2 * sl + 1]), as_bits(pmn[2 * sl])) >> sh);
+            my_hi[sl] = half_bits_to_float(select_bits(upper, as_bits(pmx[2 * sl + 1]), as_bits(pmx[2 * sl])) >> sh);
+        }
+    }
+    float gy[2], gc0[2], gz[2], gs[2], tol = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl) {
+        const _Float16 s16 = (_Float16)((my_hi[sl] - my_lo[sl]) / levels);
+        const GroupConst gc = group_const(my_lo[sl], (float)s16);
+        gy[sl] = gc.y; gc0[sl] = gc.c0; gz[sl] = gc.z; gs[sl] = gc.s;
+        tol = fmaxf(tol, gc.tol);
+        const int64_t o = ((unit * p.cap_tiles + dst_tile) * kTileTokens + tl * 8 + jj + 4 * sl) * 4 + g;
+        reinterpret_cast<_Float16*>(p.scale)[o] = s16;
+        reinterpret_cast<_Float16*>(p.zero)[o] = (_Float16)my_lo[sl];
+    }
+    tol = fmaxf(tol, dpp_f32<kQuadXor1>(tol));
+    tol = fmaxf(tol, dpp_f32<kQuadXor2>(tol));
+    const float thr = 0.5f - tol;
+    // constants of token i for every lane of the quad: from lane i & 3, slot i >> 2
+    auto quad_bcast = [](float v, auto sel) {
+        constexpr int S = decltype(sel)::value;
+        return dpp_f32<S | (S << 2) | (S << 4) | (S << 6)>(v);
+    };
+    float yi[8], ci[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        auto pick = [&](const float (&a)[2]) {
+            const float v = a[i >> 2];
+            switch (i & 3) {
+                case 0: return quad_bcast(v, std::integral_constant<int, 0>{});
+                case 1: return quad_bcast(v, std::integral_constant<int, 1>{});
+                case 2: return quad_bcast(v, std::integral_constant<int, 2>{});
+                default: return quad_bcast(v, std::integral_constant<int, 3>{});
+            }
+        };
+        yi[i] = pick(gy);
+        ci[i] = pick(gc0);
+    }
+
+    constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
+    constexpr int WPC = BITS / 2;                    // words per channel: tokens 0-7 (B = 2) or 0-3, 4-7 (B = 4)
+    uint32_t* dst = p.codes + (unit * p.cap_tiles + dst_tile) * kWords;
+    uint32_t wq[8][WPC];
+    // two channels at a time; bit of token e inside its word: (e&1)*16 + B*((e>>1) & (8/B - 1)), plus 8 for
+    // the lanes whose channels are the upper 16 of their 32-channel group (odd)
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        float dev = 0.f;
+#pragma unroll
+        for (int j = 2 * jb; j < 2 * jb + 2; ++j) {
+            // the codes of a word lie in bits 0-7 and 16-23: their sum is exact in one fp32 number
+            float acc[WPC];
+#pragma unroll
+            for (int a = 0; a < WPC; ++a) acc[a] = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int bit = (e & 1) * 16 + BITS * ((e >> 1) & (8 / BITS - 1));
+                float& dstf = acc[BITS == 2 ? 0 : (e >> 2)];
+                dstf = fmaf(encode_fast16(x[e].h[j], yi[e], ci[e], dev), (float)(1u << bit), dstf);
+            }
+#pragma unroll
+            for (int a = 0; a < WPC; ++a) wq[j][a] = (uint32_t)acc[a];
+        }
+        // a quotient next to a rounding tie anywhere in the wavefront (rare): all lanes redo these two
+        // channels with true divisions (uniform branch: the quad broadcasts inside need every lane)
+        if (__builtin_amdgcn_ballot_w64(dev > thr) != 0) {
+            float zi[8], si[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                auto pick = [&](const float (&a)[2]) {
+                    const float v = a[i >> 2];
+                    switch (i & 3) {
+                        case 0: return quad_bcast(v, std::integral_constant<int, 0>{});
+                        case 1: return quad_bcast(v, std::integral_constant<int, 1>{});
+                        case 2: return quad_bcast(v, std::integral_constant<int, 2>{});
+                        default: return quad_bcast(v, std::integral_constant<int, 3>{});
+                    }
+                };
+                zi[i] = pick(gz);
+                si[i] = pick(gs);
+            }
+#pragma unroll
+            for (int j = 2 * jb; j < 2 * jb + 2; ++j) {
+                uint32_t w[WPC];
+#pragma unroll
+                for (int a = 0; a < WPC; ++a) w[a] = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int bit = (e & 1) * 16 + BITS * ((e >> 1) & (8 / BITS - 1));
+                    w[BITS == 2 ? 0 : (e >> 2)] |= encode((float)x[e].h[j], zi[e], si[e], levels) << bit;
+                }
+#pragma unroll
+                for (int a = 0; a < WPC; ++a) wq[j][a] = w[a];
+            }
+        }
+    }
+    // combine with the lane that holds the other 16 channels of the group, then each of the two stores
+    // four of the eight channels' words
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int a = 0; a < WPC; ++a) {
+            uint32_t w = wq[j][a] << (8 * odd);
+            w |= dpp_u32<kQuadXor2>(w);
+            wq[j][a] = w;
+        }
+    const uint32_t omask = 0u - (uint32_t)odd;
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int a = 0; a < WPC; ++a) {
+            const uint32_t mine = (wq[m + 4][a] & omask) | (wq[m][a] & ~omask);     // a bitfield insert, not an indexed array
+            const int r = (seg & 1) * 8 + m + 4 * odd;             // channel % 16
+            if (BITS == 2) {
+                dst[(tl * 16 + r) * 4 + g] = mine;
+            } else {
+                const int i = g * 2 + a;
+                dst[(i >> 2) * 256 + (tl * 16 + r) * 4 + (i & 3)] = mine;
+            }
+        }
+}
+
 template <int BITS, int TG>
 __global__ __launch_bounds__(256) void quantize_keys_kernel(QuantKeyParams p) {
     quantize_key_block<BITS, TG>(p, blockIdx.x, blockIdx.y, blockIdx.z, threadIdx.x);
@@ -476,8 +806,10 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* src, size
     const size_t lo = (size_t)blockIdx.x * kStreamPiece16, hi = min(lo + kStreamPiece16, n16);
     uint32_t x = 0;
     size_t i = lo + threadIdx.x;
+    typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+    const uint4v* srcv = reinterpret_cast<const uint4v*>(src);
     for (; i + 768 < hi; i += 1024) {
-        const uint4 a = src[i], b = src[i + 256], c = src[i + 512], d = src[i + 768];
+        const uint4v a = __builtin_nontemporal_load(srcv + i), b = __builtin_nontemporal_load(srcv + i + 256), c = __builtin_nontemporal_load(srcv + i + 512), d = __builtin_nontemporal_load(srcv + i + 768);
         x ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
     }
     for (; i < hi; i += 256) {
@@ -514,11 +846,32 @@ hipError_t launch_keys_bits(const QuantKeyParams& p, hipStream_t stream) {
 
 hipError_t launch_quantize_keys(const QuantKeyParams& p, hipStream_t stream) {
     if (p.n_tiles <= 0) return hipSuccess;
+    if (p.src.ring_cap == 0 && p.tiles_per_group == 1) {        // the bulk case: one wavefront per group
+        dim3 grid((p.n_tiles + 3) / 4, p.n_kv_heads, p.batch), block(256);
+        if (p.bits == 2) quantize_keys_stream_kernel<2><<<grid, block, 0, stream>>>(p);
+        else quantize_keys_stream_kernel<4><<<grid, block, 0, stream>>>(p);
+        return hipGetLastError();
+    }
     return p.bits == 2 ? launch_keys_bits<2>(p, stream) : launch_keys_bits<4>(p, stream);
 }
 
-hipError_t launch_quantize_values(const QuantValueParams& p, hipStream_t stream) {
-    if (p.n_tokens <= 0) return hipSuccess;
+hipError_t launch_quantize_values(const QuantValueParams& p_in, hipStream_t stream) {
+    if (p_in.n_tokens <= 0) return hipSuccess;
+    QuantValueParams p = p_in;
+    if (p.src.ring_cap == 0 && p.group_blocks == 1 && p.first_token % kTileTokens == 0 && p.n_tokens >= kTileTokens) {
+        // the bulk case: whole tiles, one wavefront each; a last, partly filled tile goes the general way
+        const int whole = p.n_tokens / kTileTokens;
+        QuantValueParams pw = p;
+        pw.n_tokens = whole * kTileTokens;
+        dim3 grid((whole + 3) / 4, p.n_kv_heads, p.batch), block(256);
+        if (p.bits == 2) quantize_values_stream_kernel<2><<<grid, block, 0, stream>>>(pw);
+        else quantize_values_stream_kernel<4><<<grid, block, 0, stream>>>(pw);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+        p.src.base += (int64_t)pw.n_tokens * p.src.stride_t;
+        p.first_token += pw.n_tokens;
+        p.n_tokens -= pw.n_tokens;
+        if (p.n_tokens == 0) return hipSuccess;
+    }
     const int first_tile = p.first_token / kTileTokens;
     const int last_tile = (p.first_token + p.n_tokens - 1) / kTileTokens;
     dim3 grid((last_tile - first_tile + kValueTilesPerGroup) / kValueTilesPerGroup, p.n_kv_heads, p.batch), block(256);
