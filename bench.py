@@ -316,6 +316,20 @@ def main():
         cold_step_ms, enqueue_ms, warm_step_ms, cold_attn_ms, warm_attn_ms = measure()
     consistent = cold_attn_ms <= cold_step_ms * 1.02
 
+    # The same launch dispatched one at a time (queue idle before it, two events around it): launch
+    # latency, the event pair and the start from an idle device are all inside this figure, so it is
+    # an upper bound for a single dispatch and not the kernel's rate; reported beside the
+    # back-to-back figure for comparison with per-kernel durations of a trace.
+    isolated = []
+    for i in range(40):
+        torch.cuda.synchronize()
+        ev0.record(stream)
+        kivi.kivi_decode_attention(layout, caches[i % len(caches)], qt, w.softmax_scale, out, stream)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        isolated.append(ev0.elapsed_time(ev1) * 1e3)
+    isolated_us = sorted(isolated)[len(isolated) // 2]
+
     # Yardstick: the library's plain read-only stream kernel on this machine -- over as many bytes as
     # one attention launch moves (rotating over different buffers, so cold like the launches above)
     # and over 1 GiB (where launch and ramp-up no longer matter).
@@ -370,6 +384,7 @@ def main():
             "frac_packed_only": achieved_packed / HBM_PEAK_GBS,
             "launch_us": cold_attn_ms * 1e3,
             "launches_timed": args.roofline_launches,
+            "launch_us_one_at_a_time": isolated_us,
             "consistent_with_ms_per_step": consistent,
             "stream_read_GBs_same_bytes": stream_same_size,
             "stream_read_GBs_1GiB": stream_1gib,
