@@ -303,6 +303,10 @@ int kivi_batch_slice(const kivi_layout_t* layout, const kivi_cache_t* cache, int
  * entry point on that part of the batch (same stream, same workspace): B different lengths take B
  * calls.  Entries without any token (all counts 0) are skipped by kivi_decode_attention_ragged and
  * their `out` rows are left untouched.  kivi_decode_launches_ragged tells which applies.
+ *   The one-pair form copies the sequences' counters from host memory into the workspace with an
+ * asynchronous copy on `stream` at every call (16 bytes per sequence): do not record these two entry
+ * points into a HIP graph -- a replay would copy from host memory that is gone, and the counters
+ * change from step to step anyway.
  *   k_new, v_new, q, out   the whole batch's tensors, as for the uniform entry points
  * Errors: as for the uniform entry points; entries before the failing run have been processed.
  */

@@ -116,24 +116,30 @@ def test_larger_groups(path, bits, group, residual, length):
         _run_case(w, length, kivi.KIVI_FLUSH_ALG1, path)
 
 
-def test_quantize_entry_points_append_in_pieces():
-    """kivi_quantize_key_groups / kivi_quantize_value_tokens called piecewise (strided source,
-    value pieces that end inside a tile) build the same cache as one call."""
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("value_pieces", [((0, 5), (5, 27), (32, 1), (33, 70), (103, 89)),
+                                          ((0, 70), (70, 26), (96, 96))], ids=["ragged_pieces", "whole_tiles_and_tails"])
+def test_quantize_entry_points_append_in_pieces(bits, value_pieces):
+    """kivi_quantize_key_groups / kivi_quantize_value_tokens called piecewise (strided sources,
+    value pieces that end inside a tile, and pieces of whole tiles followed by a partly filled one:
+    the one-wavefront-per-tile kernels and the general ones write into the same tiles) build the same
+    cache as one call."""
     torch = gh.require_gpu()
-    w = scaled(CONFIGS["llama7b"], name="pieces", batch=2, n_q_heads=2, n_kv_heads=2, seed=31)
+    w = scaled(CONFIGS["llama7b"], name="pieces", batch=2, n_q_heads=2, n_kv_heads=2, bits=bits, seed=31)
     n = 192
     k = workloads.keys(w, n)
     v = workloads.values(w, n)
     layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, 256, 192)
     cache = kivi.Cache(layout)
-    # source with padded token stride and swapped (h, b) memory order
-    kt = torch.zeros(w.n_kv_heads, w.batch, n, 136, dtype=torch.float16, device="cuda")
-    kt[..., :128] = torch.from_numpy(k).cuda().permute(1, 0, 2, 3)
-    kt = kt.permute(1, 0, 2, 3)[..., :128]
-    vt = torch.from_numpy(v).cuda()
+    # sources with padded token stride and swapped (h, b) memory order
+    def strided(x):
+        t = torch.zeros(w.n_kv_heads, w.batch, n, 136, dtype=torch.float16, device="cuda")
+        t[..., :128] = torch.from_numpy(x).cuda().permute(1, 0, 2, 3)
+        return t.permute(1, 0, 2, 3)[..., :128]
+    kt, vt = strided(k), strided(v)
     for start, cnt in ((0, 64), (64, 32), (96, 96)):
         kivi.kivi_quantize_key_groups(layout, kt[:, :, start:], cnt, cache)
-    for start, cnt in ((0, 5), (5, 27), (32, 1), (33, 70), (103, 89)):
+    for start, cnt in value_pieces:
         kivi.kivi_quantize_value_tokens(layout, vt[:, :, start:], cnt, cache)
     torch.cuda.synchronize()
     assert (cache.c.n_kq, cache.c.n_vq) == (n, n)
