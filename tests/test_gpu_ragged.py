@@ -141,3 +141,43 @@ def test_ragged_64_distinct_lengths(bits, rep):
             print(f"case ragged64: step {step} ok, worst abs err {worst:.3e}", flush=True)
     for b in range(w.batch):
         gh.compare_quantized_state(_SeqView(cache, b, states[b]), oracles[b])
+
+
+@pytest.mark.parametrize("batch,n_q_heads,n_kv_heads", [(300, 2, 1), (6, 32, 2)], ids=["batch300", "16_heads_per_kv_head"])
+def test_ragged_wide_batches_and_groups(batch, n_q_heads, n_kv_heads):
+    """The one-pair form past its internal piece sizes: more sequences than one host-to-device piece
+    of counters holds (256), and more query heads per kv-head than one launch serves (8: a pair of
+    launches per group of 8).  Attention only, every sequence against an oracle cache of its own."""
+    torch = gh.require_gpu()
+    rng = np.random.default_rng(batch)
+    prompts = [int(x) for x in rng.integers(1, 700, size=batch)]
+    prompts[0] = 1                                  # one fp16 row, nothing quantised
+    prompts[-1] = 699
+    w = scaled(CONFIGS["stream"], name="raggedwide", batch=batch, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, residual=64,
+               prompt=0, decode_steps=0, seed=808 + batch)
+    total = max(prompts)
+    k, v = workloads.keys(w, total), workloads.values(w, total)
+    layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, gh.round_up(total, 32), 128)
+    cache = kivi.Cache(layout)
+    states = kivi.make_states(w.batch)
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    oracles = []
+    print(f"case raggedwide batch={batch} heads={n_q_heads}/{n_kv_heads}: per-sequence prefill", flush=True)
+    for b, n in enumerate(prompts):
+        oc = ko.StreamingCache(1, w.n_kv_heads, 128, w.bits, w.group, w.residual, "window")
+        sl = kivi.CacheSlice(cache, b, 1)
+        kivi.kivi_prefill(sl.layout, kt[b:b + 1], vt[b:b + 1], n, sl, kivi.KIVI_FLUSH_WINDOW)
+        states[b] = sl.state()
+        oc.prefill(k[b:b + 1, :, :n], v[b:b + 1, :, :n])
+        oracles.append(oc)
+    groups = -(-(n_q_heads // n_kv_heads) // 8)
+    assert kivi.kivi_decode_launches_ragged(layout, states) == 2 * groups
+    q = workloads.queries(w, 0)
+    out = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    kivi.kivi_decode_attention_ragged(layout, cache, states, torch.from_numpy(q).cuda(), w.softmax_scale, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    worst = 0.0
+    for b in range(w.batch):
+        worst = max(worst, gh.check_close(got[b:b + 1], oracles[b].attention(q[b:b + 1], w.softmax_scale), f"seq {b} (n={prompts[b]})"))
+    print(f"case raggedwide: worst abs err {worst:.3e}", flush=True)
