@@ -401,12 +401,13 @@ int ragged_attention_fast(const kivi_layout_t* l, const kivi_cache_t* c, const k
     const int rep_total = l->n_q_heads / l->n_kv_heads;
     const int rep_launch = std::min(rep_total, kMaxRep);
     const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
-    int max_tiles_a = 0, max_tiles_b = 0;
+    int max_tiles_a = 0, max_tiles_b = 0, min_tiles_a = INT32_MAX;
     for (int b = 0; b < l->batch; ++b) {
         const kivi_seq_state_t& x = st[b];
         if (x.n_kq != x.n_vq || x.n_kr != x.n_vr || x.n_kr < 1 || x.n_kq % kTileTokens != 0) return kNotApplicable;
         const int tiles_a = x.n_kq / kTileTokens;
         max_tiles_a = std::max(max_tiles_a, tiles_a);
+        min_tiles_a = std::min(min_tiles_a, tiles_a);
         max_tiles_b = std::max(max_tiles_b, ceil_div(x.n_kq + x.n_kr, kTileTokens) - tiles_a);
     }
     if (max_tiles_a < 1 || !residual_rows_possible(max_tiles_b, rep_variant)) return kNotApplicable;
@@ -444,6 +445,7 @@ int ragged_attention_fast(const kivi_layout_t* l, const kivi_cache_t* c, const k
     p.counters = reinterpret_cast<int32_t*>(ws);
     int32_t* dev_state = reinterpret_cast<int32_t*>(ws + counter_bytes(l));
     p.seq_state = dev_state;
+    p.ragged_min_tiles = min_tiles_a;
     p.part_o = reinterpret_cast<float*>(ws + counter_bytes(l) + seq_state_bytes(l));
     p.part_ml = p.part_o + rows * kHeadDim;
 

@@ -1136,6 +1136,290 @@ int resident_workgroups() {
     return cus * per_cu;
 }
 
+// ---- the all-quantised part with one (batch, kv-head) unit per WAVEFRONT ----
+// Second launch of the two-launch form for batches with at least as many units as the chip holds
+// wavefronts of this kernel.  In decode_mfma_kernel<..., kQuantisedOnly> the four wavefronts of a
+// workgroup share every unit (each takes every 4th tile), so leaving a unit means merging four
+// states through LDS between workgroup barriers and staging the next query behind another one:
+// 2.0-2.3 us per unit at the streaming configuration (device timestamps), four times per
+// workgroup, 13 % of the launch.  Here a wavefront walks whole units by itself, four consecutive
+// tiles at a time through the same register pipeline (next group's data requested while the current
+// one is consumed, across unit borders; next unit's query and the first launch's part requested one
+// unit ahead): no barrier, no cross-wavefront merge, no device-scope traffic; leaving a unit is
+// a reduction inside the wavefront and the output store.  Same tile arithmetic (the device functions
+// above), same running-maximum softmax, same merge with the part of the fp16-row launch.
+template <int BITS, int REP, int OCC>
+__global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParams p) {
+    constexpr int kSlots = 4;
+    constexpr int kStage = REP > 2 ? 1 : 2;
+    using WL = WaveLds<REP, kStage>;
+    constexpr int NC = 2 * REP, SS = WL::kStageSlots;
+    constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
+    constexpr int kLaneWords = BITS * 2;
+    constexpr int kIdx = 2 * REP;                       // output elements per lane: (head, channel lane + 64 k)
+    __shared__ WL sm_w[4];
+    __shared__ __align__(16) float sm_q[4][REP][kHeadDim];
+    __shared__ __align__(16) __half sm_qf[4][NC][kKRow];
+    __shared__ float sm_zs[4][REP][4];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int n = lane & 15, rq = lane >> 4, ncol = n & (NC - 1);
+    WL& wl = sm_w[wave];
+    const int rep = p.rep_here, rep_total = p.n_q_heads / p.n_kv_heads;
+    const int units = p.batch * p.n_kv_heads;
+    const int n_waves = (int)gridDim.x * 4, gw = (int)blockIdx.x * 4 + wave;
+    // all-quantised tiles of a unit (>= 1): the plan's, or -- a batch of different lengths -- the
+    // sequence's own from seq_state (the host has checked that every sequence has at least one)
+    auto tiles_of = [&](int u) -> int {
+        return p.seq_state ? __builtin_amdgcn_readfirstlane(p.seq_state[4 * (u / p.n_kv_heads)]) / kTileTokens : p.plan.tiles_a;
+    };
+    const int row_stride = p.plan.n_splits();           // workspace rows per (batch, query head); row 0: the fp16-row launch's part
+    if (gw >= units) return;                            // whole wavefronts leave; the kernel has no barrier
+
+    auto first_q_head = [&](int u) -> int { return (u % p.n_kv_heads) * rep_total + p.q_head0; };
+    auto batch_of = [&](int u) -> int { return u / p.n_kv_heads; };
+
+    uint32_t kw[kSlots][kLaneWords], vw[kSlots][kLaneWords];
+    __half2 ks2[kSlots], vs2[kSlots], vz2[kSlots];
+    half8 zf[4];
+    // the group whose data is being requested ("next"); requests are unconditional (past the end they
+    // re-read tile 0 of unit 0) so that the compiler counts the outstanding loads exactly
+    int nx_u = gw, nx_g = 0, nx_tiles = tiles_of(gw);
+    bool nx_ok = true;
+    auto next_tile = [&](int slot) -> int64_t {
+        return nx_ok ? (int64_t)nx_u * p.cap_tiles + min(nx_g * kSlots + slot, nx_tiles - 1) : 0;
+    };
+    auto advance_next = [&]() {
+        if (++nx_g * kSlots >= nx_tiles) {
+            nx_g = 0;
+            nx_u += n_waves;
+            nx_ok = nx_u < units;
+            nx_tiles = nx_ok ? tiles_of(nx_u) : 1;
+        }
+    };
+    auto request_zero_rows = [&]() {
+        const int64_t tile = next_tile(min(n, kSlots - 1));                // A row n = slot n
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            zf[ks] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8));
+    };
+    auto request_key_slot = [&](int i) {
+        const int64_t tile = next_tile(i);
+        load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
+        ks2[i] = nt_half2(p.k_scale + tile * kHeadDim + 2 * lane);
+    };
+    auto request_value_slot = [&](int i) {
+        const int64_t tile = next_tile(i);
+        load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
+        vs2[i] = nt_half2(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
+        vz2[i] = nt_half2(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+    };
+    // query and fp16-row part of a unit: lane l holds the elements (head k / 2, channel l + 64 (k % 2))
+    __half q_pre[kIdx];
+    float pre_m[kIdx], pre_l[kIdx], pre_o[kIdx];
+    auto request_unit = [&](int u_req) {
+        const int u = min(u_req, units - 1);                              // unconditional loads (clamped)
+        const int64_t row0 = (int64_t)batch_of(u) * p.n_q_heads + first_q_head(u);
+#pragma unroll
+        for (int k = 0; k < kIdx; ++k) {
+            const int64_t row = row0 + min(k >> 1, rep - 1);
+            const int c = lane + 64 * (k & 1);
+            q_pre[k] = p.q[row * kHeadDim + c];
+            pre_m[k] = p.part_ml[row * row_stride * 2 + 0];
+            pre_l[k] = p.part_ml[row * row_stride * 2 + 1];
+            pre_o[k] = p.part_o[row * row_stride * kHeadDim + c];
+        }
+    };
+
+    float4v acc[8];
+    float zacc[REP][2], m_run[REP], l_lane[REP], qpf[REP][2];
+
+    // probabilities of the wavefront's 128 token slots against the running maximum (2 slots per lane)
+    auto softmax_step = [&](int cnt) {
+        const int slot = lane >> 4;
+        const bool live = slot < cnt;
+        float a0[REP], a1[REP], scale_lane = 1.f;
+        bool any_rescale = false;
+#pragma unroll
+        for (int hh = 0; hh < REP; ++hh) {
+            const float2 hi = *reinterpret_cast<const float2*>(&wl.lr[2 * hh][2 * lane]);
+            const float2 lo = *reinterpret_cast<const float2*>(&wl.lr[2 * hh + 1][2 * lane]);
+            const float zt = join_hi_lo(wl.zt[2 * hh][slot], wl.zt[2 * hh + 1][slot]);
+            a0[hh] = live ? fmaf(join_hi_lo(hi.x, lo.x), kUnscale, zt) : -INFINITY;
+            a1[hh] = live ? fmaf(join_hi_lo(hi.y, lo.y), kUnscale, zt) : -INFINITY;
+            const float mx = wave_max(fmaxf(a0[hh], a1[hh]));
+            if (mx > m_run[hh]) {                       // wave-uniform: the running maximum grows
+                const float f = __expf(m_run[hh] - mx); // 0 on the first group (m_run = -inf)
+                l_lane[hh] *= f;
+                zacc[hh][0] *= f; zacc[hh][1] *= f;
+                if ((n >> 1) == hh) scale_lane = f;
+                any_rescale = true;
+                m_run[hh] = mx;
+            }
+        }
+        if (any_rescale) {
+#pragma unroll
+            for (int u8 = 0; u8 < 8; ++u8)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[u8][j] *= scale_lane;
+        }
+#pragma unroll
+        for (int hh = 0; hh < REP; ++hh) {
+            const float p0 = __expf(a0[hh] - m_run[hh]), p1 = __expf(a1[hh] - m_run[hh]);   // a group has at least one live slot
+            *reinterpret_cast<float2*>(&wl.lr[2 * hh][2 * lane]) = make_float2(p0, p1);
+            l_lane[hh] += p0 + p1;
+        }
+        wave_lds_sync();
+    };
+
+    request_unit(gw);
+    request_zero_rows();
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) request_key_slot(i);
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) request_value_slot(i);
+
+    for (int u = gw; u < units; u += n_waves) {
+        // ---- enter the unit: query operands of this wavefront ----
+        float um[kIdx], ul[kIdx], uo[kIdx];              // the fp16-row launch's part of this unit
+#pragma unroll
+        for (int k = 0; k < kIdx; ++k) {
+            const int hh = k >> 1, c = lane + 64 * (k & 1);
+            const float x = hh < rep ? p.softmax_scale * __half2float(q_pre[k]) : 0.f;
+            __half hi, lo;
+            split_hi_lo(x, hi, lo);
+            sm_q[wave][hh][c] = x;
+            sm_qf[wave][2 * hh][c] = hi;
+            sm_qf[wave][2 * hh + 1][c] = lo;
+            um[k] = pre_m[k]; ul[k] = pre_l[k]; uo[k] = pre_o[k];
+        }
+        wave_lds_sync();
+        request_unit(u + n_waves);                      // one unit ahead
+        {
+            const float pf = inv_pos_factor<BITS>(lane & 3);
+#pragma unroll
+            for (int hh = 0; hh < REP; ++hh) {
+                qpf[hh][0] = sm_q[wave][hh][2 * lane] * pf;
+                qpf[hh][1] = sm_q[wave][hh][2 * lane + 1] * pf;
+            }
+        }
+#pragma unroll
+        for (int u8 = 0; u8 < 8; ++u8) acc[u8] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int hh = 0; hh < REP; ++hh) {
+            zacc[hh][0] = zacc[hh][1] = 0.f;
+            m_run[hh] = -INFINITY;
+            l_lane[hh] = 0.f;
+        }
+
+        const int tiles = tiles_of(u);
+        for (int g = 0; g * kSlots < tiles; ++g) {
+            const int cnt = min(kSlots, tiles - g * kSlots);          // tiles of this group
+            advance_next();                                             // the requests below are for the group after this one
+            // key z-terms of the four slots: one 16x16x128 product
+            {
+                float4v d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const half8 bq = *reinterpret_cast<const half8*>(&sm_qf[wave][ncol][ks * 32 + rq * 8]);
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(zf[ks], bq, d, 0, 0, 0);
+                }
+                if (n < NC && rq == 0) *reinterpret_cast<float4*>(&wl.zt[n][0]) = make_float4(d[0], d[1], d[2], d[3]);
+            }
+            request_zero_rows();
+            // ---- raw logits ----
+#pragma unroll
+            for (int c0 = 0; c0 < kSlots; c0 += SS) {
+#pragma unroll
+                for (int sl = 0; sl < SS; ++sl) stage_key_operand<REP>(wl.b + sl * WL::kKSlot, ks2[c0 + sl], qpf, lane);
+                wave_lds_sync();
+#pragma unroll
+                for (int sl = 0; sl < SS; ++sl) {
+                    key_tile_mfma<BITS, REP>(kw[c0 + sl], wl.b + sl * WL::kKSlot, wl.lr, c0 + sl, lane);
+                    request_key_slot(c0 + sl);                          // the slot's registers are free again
+                }
+                wave_lds_sync();
+            }
+            wave_lds_sync();
+            softmax_step(cnt);
+            // ---- outputs ----
+#pragma unroll
+            for (int c0 = 0; c0 < kSlots; c0 += SS) {
+#pragma unroll
+                for (int sl = 0; sl < SS; ++sl)
+                    stage_value_operand<BITS, REP, false>(wl.b + sl * WL::kVSlot, vs2[c0 + sl], vz2[c0 + sl],
+                                                          kTileTokens, wl.lr, c0 + sl, zacc, lane);
+                wave_lds_sync();
+#pragma unroll
+                for (int sl = 0; sl < SS; ++sl) {
+                    value_tile_mfma<BITS, REP>(vw[c0 + sl], wl.b + sl * WL::kVSlot, acc, lane);
+                    request_value_slot(c0 + sl);
+                }
+                wave_lds_sync();
+            }
+            wave_lds_sync();
+        }
+
+        // ---- leave the unit: raw matrix-core outputs and z-term sums through this wavefront's LDS ----
+        if (n < NC) {
+#pragma unroll
+            for (int u8 = 0; u8 < 8; ++u8)
+                *reinterpret_cast<float4*>(&wl.lr[n][u8 * 16 + rq * 4]) =
+                    make_float4(acc[u8][0], acc[u8][1], acc[u8][2], acc[u8][3]);
+        }
+        float l_w[REP];
+#pragma unroll
+        for (int hh = 0; hh < REP; ++hh) {
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                float zz = zacc[hh][k];
+                zz += dpp<kDppXor2>(zz); zz += dpp<kDppRor4>(zz); zz += dpp<kDppRor8>(zz);
+                zz += __shfl_xor(zz, 16); zz += __shfl_xor(zz, 32);
+                if (lane < 2) sm_zs[wave][hh][lane * 2 + k] = zz;      // lane 0: groups 0,1; lane 1: groups 2,3
+            }
+            l_w[hh] = wave_sum(l_lane[hh]);
+        }
+        wave_lds_sync();
+        const int64_t row0 = (int64_t)batch_of(u) * p.n_q_heads + first_q_head(u);
+#pragma unroll
+        for (int k = 0; k < kIdx; ++k) {
+            const int hh = k >> 1, c = lane + 64 * (k & 1);
+            if (hh < rep) {
+                float mm = m_run[hh], ll = l_w[hh];
+                float oo = fmaf(join_hi_lo(wl.lr[2 * hh][c], wl.lr[2 * hh + 1][c]), kUnscale, sm_zs[wave][hh][c >> 5]);
+                if (um[k] > -INFINITY) {                 // the fp16-row launch's part (the window is never empty in this form)
+                    const float mn = fmaxf(mm, um[k]);
+                    const float f_old = __expf(mm - mn), f_new = __expf(um[k] - mn);
+                    ll = fmaf(ll, f_old, ul[k] * f_new);
+                    oo = fmaf(oo, f_old, uo[k] * f_new);
+                }
+                p.out[(row0 + hh) * kHeadDim + c] = oo / ll;
+            }
+        }
+        wave_lds_sync();                                 // this wavefront's LDS is reused by its next unit
+    }
+}
+
+// Wavefronts the device holds at once for decode_wave_units_kernel (per device, as above).
+template <int BITS, int REP, int OCC>
+int resident_wave_unit_workgroups() {
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256 * OCC;
+    const bool keep = dev >= 0 && dev < kMaxDevices;
+    if (keep) {
+        const int c = cached[dev].load(std::memory_order_relaxed);
+        if (c > 0) return c;
+    }
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_wave_units_kernel<BITS, REP, OCC>, 256, 0) != hipSuccess ||
+        cus <= 0 || per_cu <= 0)
+        return 256 * OCC;
+    if (keep) cached[dev].store(cus * per_cu, std::memory_order_relaxed);
+    return cus * per_cu;
+}
+
 template <int BITS, int REP, int SLOTS, int OCC, int HSHIFT = 0>
 hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
@@ -1184,6 +1468,19 @@ hipError_t launch_two(DecodeParams p, hipStream_t stream) {
     p.cost_b = 1;
     p.cost_unit = p.plan.n_splits_a;
     p.total_cost = total_a;
+    // One unit per wavefront where that fills the chip evenly: at least as many units as resident
+    // wavefronts, and the last round of units at most 12 % short of a full one.
+    if constexpr (REP <= 4) {
+        if (!p.seq_state || p.ragged_min_tiles >= 1) {
+            const int64_t waves = 4 * (int64_t)resident_wave_unit_workgroups<BITS, REP, OCC>();
+            const int64_t rounds = (units + waves - 1) / waves;
+            if (units >= waves && rounds * waves * 100 <= units * 112 && p.plan.tiles_a >= 1 && p.plan.n_splits_b == 1) {
+                const int grid = (int)std::min<int64_t>(waves / 4, (units + 3) / 4);
+                decode_wave_units_kernel<BITS, REP, OCC><<<grid, 256, 0, stream>>>(p);
+                return hipGetLastError();
+            }
+        }
+    }
     if (p.seq_state) {
         const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedRagged>(), total_a);
         decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedRagged><<<grid, 256, 0, stream>>>(p);

@@ -68,6 +68,26 @@ def test_grouped_query(path, bits, rep):
     _run_case(w, 6000, kivi.KIVI_FLUSH_ALG1, path, heads=[(0, 1), (1, 0)])
 
 
+@pytest.mark.parametrize("bits,rep,batch,n_kv,length", [
+    (2, 1, 256, 8, 300),      # 2048 units = one per resident wavefront; 7 all-quantised tiles (a short last group of 3)
+    (4, 1, 272, 8, 200),      # 2176 units: a second, sparse round of units; 4 tiles
+    (2, 2, 128, 16, 166),     # two query heads per kv-head; 3 tiles (fewer than one group)
+    (4, 2, 256, 8, 420),
+    (2, 4, 256, 8, 260),      # four query heads per kv-head
+    (2, 3, 256, 8, 230),      # three heads on the four-head instantiation
+    (2, 16, 256, 8, 200),     # 16 heads per kv-head: two passes of eight on the shared-unit form
+], ids=["u2048_b2", "u2176_b4", "rep2_b2", "rep2_b4", "rep4_b2", "rep3_b2", "rep16_b2"])
+def test_many_units_one_per_wavefront(bits, rep, batch, n_kv, length):
+    """Batches with at least as many (batch, kv-head) units as the chip holds wavefronts: the second
+    launch of the two-launch form gives every wavefront whole units (decode_wave_units_kernel; with
+    more than four heads per launch the shared-unit form).  Every unit against the oracle, state bit-exact."""
+    w = scaled(CONFIGS["stream"], name="many_units", batch=batch, n_q_heads=n_kv * rep, n_kv_heads=n_kv, bits=bits,
+               residual=64, seed=2600 + bits + rep)
+    print(f"case many_units bits={bits} rep={rep} units={batch * n_kv} L={length}", flush=True)
+    _run_case(w, length, kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_DECODE_AUTO)
+    _run_case(w, length, kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_DECODE_MFMA_TWO)
+
+
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("n_kv,rep", [(2, 9), (2, 16), (1, 71)])

@@ -143,7 +143,8 @@ def test_ragged_64_distinct_lengths(bits, rep):
         gh.compare_quantized_state(_SeqView(cache, b, states[b]), oracles[b])
 
 
-@pytest.mark.parametrize("batch,n_q_heads,n_kv_heads", [(300, 2, 1), (6, 32, 2)], ids=["batch300", "16_heads_per_kv_head"])
+@pytest.mark.parametrize("batch,n_q_heads,n_kv_heads", [(300, 2, 1), (6, 32, 2), (256, 16, 8)],
+                         ids=["batch300", "16_heads_per_kv_head", "2048_units"])
 def test_ragged_wide_batches_and_groups(batch, n_q_heads, n_kv_heads):
     """The one-pair form past its internal piece sizes: more sequences than one host-to-device piece
     of counters holds (256), and more query heads per kv-head than one launch serves (8: a pair of
@@ -153,6 +154,10 @@ def test_ragged_wide_batches_and_groups(batch, n_q_heads, n_kv_heads):
     prompts = [int(x) for x in rng.integers(1, 700, size=batch)]
     prompts[0] = 1                                  # one fp16 row, nothing quantised
     prompts[-1] = 699
+    if batch * n_kv_heads >= 2048:
+        # as many units as the chip holds wavefronts and every sequence with quantised tokens: the
+        # second launch gives every wavefront whole units, each with its own sequence's length
+        prompts = [max(x, 100) for x in prompts]
     w = scaled(CONFIGS["stream"], name="raggedwide", batch=batch, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, residual=64,
                prompt=0, decode_steps=0, seed=808 + batch)
     total = max(prompts)
