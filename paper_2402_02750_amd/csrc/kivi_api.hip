@@ -57,7 +57,10 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // the kv-head's query heads, should a launch serve parts of the group as units of their own -- padded
 // to 256 bytes.
 size_t counter_bytes(const kivi_layout_t* l) {
-    return ((size_t)l->batch * l->n_kv_heads * 4 * sizeof(int32_t) + 255) / 256 * 256;
+    // one counter per unit of the work axis: up to 4 parts of a kv-head's query heads (head split), or
+    // one per run of kMaxRep heads of a wider group
+    const int groups = std::max(4, ceil_div(l->n_q_heads / std::max(l->n_kv_heads, 1), kMaxRep));
+    return ((size_t)l->batch * l->n_kv_heads * groups * sizeof(int32_t) + 255) / 256 * 256;
 }
 
 // Room for the per-sequence counters of a batch of different lengths (16 bytes per sequence, padded
@@ -281,6 +284,15 @@ int head_split_shift(const kivi_layout_t* l, const SplitPlan& plan, int path, bo
     return chunks <= (int64_t)mfma_geometry(l->bits, 4).resident_workgroups * max_chunks_per_workgroup ? 1 : 0;
 }
 
+// Runs of kMaxRep query heads a kv-head's group is served in by ONE launch of the matrix-core
+// family's single-launch form (1: the group fits one run, or the form is not the single launch:
+// then a wider group takes one launch, or pair of launches, per run).
+int wide_group_runs(const kivi_layout_t* l, int path, bool two_launches) {
+    const int rep_total = l->n_q_heads / l->n_kv_heads;
+    if (path != KIVI_DECODE_MFMA || two_launches || rep_total <= kMaxRep) return 1;
+    return ceil_div(rep_total, kMaxRep);
+}
+
 // Launch the attention of q over cache state `c` (already validated).  k_new / v_new non-null: the
 // rows of token length-1 are not in the rings yet and the (matrix-core) kernel puts them there.
 // flush_k / flush_v non-null (two-launch form only): the residual flush that produced state `c` has
@@ -311,6 +323,7 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     const bool two = wants_two_launches(l, c, path);
     p.plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
     p.two_launches = two ? 1 : 0;
+    p.head_groups = wide_group_runs(l, path, two);
     if ((flush_k || flush_v) && !(two && flush_k && flush_v)) return KIVI_ERR_INVALID_ARG;
     p.flush_k = flush_k;
     p.flush_v = flush_v;
@@ -327,6 +340,13 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     // matrix-core kernel leaves its counters at zero).  Only the first one appends the new token.
     const int rep_total = l->n_q_heads / l->n_kv_heads;
     p.rep_variant = std::min(rep_total, kMaxRep);
+    if (p.head_groups > 1) {
+        // a group wider than kMaxRep heads in the single-launch form: its runs of kMaxRep heads are
+        // units of ONE launch (they read the same cache, which the caches serve after the first)
+        p.q_head0 = 0;
+        p.rep_here = kMaxRep;
+        return hip_status(launch_decode_mfma(p, hs));
+    }
     if (const int shift = head_split_shift(l, p.plan, path, two)) {
         p.head_split = shift;
         p.q_head0 = 0;
@@ -609,8 +629,13 @@ int kivi_decode_plan(const kivi_layout_t* l, const kivi_cache_t* c, kivi_decode_
     const bool two = wants_two_launches(l, c, path);
     const SplitPlan plan = plan_splits(l, c, path == KIVI_DECODE_MFMA, two);
     out->family = path;
-    out->launches = path == KIVI_DECODE_MFMA ? (two ? 2 : 1) : 2;       // vector-ALU family: decode + merge
-    out->units_per_kv_head = 1 << head_split_shift(l, plan, path, two);
+    // launches: a group wider than kMaxRep heads takes one pass per run of kMaxRep heads, except in the
+    // matrix-core family's single-launch form, where the runs are units of one launch
+    const int rep_total = l->n_q_heads / l->n_kv_heads;
+    const int runs = wide_group_runs(l, path, two);
+    const int passes = runs > 1 ? 1 : ceil_div(rep_total, kMaxRep);
+    out->launches = path == KIVI_DECODE_MFMA ? (two ? 2 : 1) * passes : passes + 1;      // vector-ALU family: decodes + merge
+    out->units_per_kv_head = runs > 1 ? runs : 1 << head_split_shift(l, plan, path, two);
     out->splits_quantised = plan.n_splits_a;
     out->splits_fp16 = plan.n_splits_b;
     out->tiles_per_split_quantised = plan.tiles_per_split_a;

@@ -294,6 +294,7 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
 // number of all-quantised tiles from p.seq_state); an instantiation of its own so that batches of
 // one length pay nothing for it.
 constexpr int kBothPhases = 0, kQuantisedOnly = 1, kQuantisedRagged = 2;
+constexpr int kRuntimeHeadGroups = 15;      // value of HSHIFT: the number of head runs per kv-head is a launch parameter
 
 template <int BITS, int REP, int SLOTS, int OCC, int MODE, int HSHIFT = 0>
 __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
@@ -337,11 +338,19 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     // HSHIFT > 0: a unit of the work axis is (batch, kv-head, one of 2^HSHIFT equal parts of the
     // kv-head's query heads) -- unit u reads the cache of (batch, kv-head) u >> HSHIFT and serves the
     // query heads (u & (2^HSHIFT - 1)) * rep .. + rep of its group; parts, counters and held results go by u.
-    constexpr int kPartMask = (1 << HSHIFT) - 1;
-    auto kv_unit = [&](int u) -> int { return u >> HSHIFT; };
+    // HSHIFT == kRuntimeHeadGroups: groups wider than REP heads (multi-query attention) in ONE launch --
+    // a unit is (batch, kv-head, one of p.head_groups runs of REP consecutive query heads; the last run
+    // may be shorter): every run reads the same cache, which the chip's caches serve after the first.
+    constexpr bool kRunGroups = HSHIFT == kRuntimeHeadGroups;
+    constexpr int kPartMask = kRunGroups ? 0 : (1 << HSHIFT) - 1;
+    const int n_groups = kRunGroups ? p.head_groups : 1;
+    auto kv_unit = [&](int u) -> int { return kRunGroups ? u / n_groups : u >> HSHIFT; };
+    auto part_of = [&](int u) -> int { return kRunGroups ? u - (u / n_groups) * n_groups : u & kPartMask; };
     auto first_q_head = [&](int u) -> int {
-        return (kv_unit(u) % p.n_kv_heads) * rep_total + p.q_head0 + (u & kPartMask) * rep;
+        return (kv_unit(u) % p.n_kv_heads) * rep_total + p.q_head0 + part_of(u) * (kRunGroups ? REP : rep);
     };
+    // live query heads of unit u on this instantiation
+    auto rep_of = [&](int u) -> int { return kRunGroups ? min(REP, rep_total - part_of(u) * REP) : rep; };
     auto batch_of = [&](int u) -> int { return kv_unit(u) / p.n_kv_heads; };
     // chunks per unit on this launch's cost axis: all-quantised / with fp16 rows
     const int n_a = p.plan.n_splits_a, n_b = kQOnly ? 0 : p.plan.n_splits_b;
@@ -491,7 +500,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         const int b = batch_of(u);
 #pragma unroll
         for (int k = 0; k < kIdx; ++k) {
-            const int idx = min(tid + 256 * k, rep * kHeadDim - 1);        // unconditional loads (clamped)
+            const int idx = min(tid + 256 * k, rep_of(u) * kHeadDim - 1);  // unconditional loads (clamped)
             q_pre[k] = p.q[((int64_t)b * p.n_q_heads + hq0 + idx / kHeadDim) * kHeadDim + idx % kHeadDim];
         }
     };
@@ -501,7 +510,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         const int b = batch_of(u);
 #pragma unroll
         for (int k = 0; k < kIdx; ++k) {
-            const int idx = min(tid + 256 * k, rep * kHeadDim - 1);        // unconditional loads (clamped)
+            const int idx = min(tid + 256 * k, rep_of(u) * kHeadDim - 1);  // unconditional loads (clamped)
             const int64_t row = ((int64_t)b * p.n_q_heads + hq0 + idx / kHeadDim) * cpu;
             pre_m[k] = p.part_ml[row * 2 + 0];
             pre_l[k] = p.part_ml[row * 2 + 1];
@@ -633,9 +642,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         if constexpr (kQOnly && kPrefetchPart) {
 #pragma unroll
             for (int k = 0; k < kIdx; ++k)
-                if (tid + 256 * k < rep * kHeadDim) finish_element(tid + 256 * k, pre_m[k], pre_l[k], pre_o[k]);
+                if (tid + 256 * k < rep_of(u) * kHeadDim) finish_element(tid + 256 * k, pre_m[k], pre_l[k], pre_o[k]);
         } else {
-            for (int idx = tid; idx < rep * kHeadDim; idx += 256) {
+            for (int idx = tid; idx < rep_of(u) * kHeadDim; idx += 256) {
                 float p0_m = -INFINITY, p0_l = 0.f, p0_o = 0.f;
                 if (merge_rows_parts) {
                     const int64_t row = ((int64_t)b * p.n_q_heads + hq0 + idx / kHeadDim) * cpu;
@@ -668,7 +677,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             }
             __syncthreads();
             if (sm_last) {
-                for (int idx = tid; idx < rep * kHeadDim; idx += 256) {
+                for (int idx = tid; idx < rep_of(u) * kHeadDim; idx += 256) {
                     const int hh = idx / kHeadDim, c = idx % kHeadDim;
                     const int64_t row = (int64_t)b * p.n_q_heads + hq0 + hh;
                     const float* ml = p.part_ml + row * row_stride * 2;
@@ -720,12 +729,12 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 #pragma unroll
             for (int k = 0; k < kIdx; ++k) {           // the query was requested one unit ahead
                 const int i = tid + 256 * k;
-                if (i < REP * kHeadDim) stage(i, i / kHeadDim < rep ? p.softmax_scale * __half2float(q_pre[k]) : 0.f);
+                if (i < REP * kHeadDim) stage(i, i / kHeadDim < rep_of(u) ? p.softmax_scale * __half2float(q_pre[k]) : 0.f);
             }
         } else {
             for (int i = tid; i < REP * kHeadDim; i += 256) {
                 const int hh = i / kHeadDim, c = i % kHeadDim;
-                stage(i, hh < rep ? p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f);
+                stage(i, hh < rep_of(u) ? p.softmax_scale * __half2float(p.q[((int64_t)b * p.n_q_heads + hq0 + hh) * kHeadDim + c]) : 0.f);
             }
         }
         unit_barrier();
@@ -869,7 +878,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             if (fused_append) {
                 const int last = p.length - 1, last_tile = last / kTileTokens;
                 owns_new = last_tile >= tile0 && last_tile < tile0 + n_tiles && ((last_tile - tile0) & 3) == wave && lane < 32 &&
-                           (u & kPartMask) == 0;      // the parts of a kv-head's group would all store the same rows
+                           part_of(u) == 0;           // the parts of a kv-head's group would all store the same rows
                 if (owns_new) {
                     const bool is_v = lane >= 16;
                     const int slot = is_v ? ring_slot(p.v_r_start, last - p.n_vq, p.cap_r)
@@ -920,7 +929,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                         }
 #pragma unroll
                         for (int hh = 0; hh < REP; ++hh) {
-                            const half8 qh = hh < rep ? *reinterpret_cast<const half8*>(p.q + qrow + hh * kHeadDim + seg * 8) : half8{};
+                            const half8 qh = hh < rep_of(u) ? *reinterpret_cast<const half8*>(p.q + qrow + hh * kHeadDim + seg * 8) : half8{};
 #pragma unroll
                             for (int j = 0; j < RB; ++j) {
                                 const int tl = (j0 + j) * 4 + row;
@@ -1423,7 +1432,8 @@ int resident_wave_unit_workgroups() {
 template <int BITS, int REP, int SLOTS, int OCC, int HSHIFT = 0>
 hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
-    const int64_t units = ((int64_t)p.batch * p.n_kv_heads) << HSHIFT;
+    const int64_t units = HSHIFT == kRuntimeHeadGroups ? (int64_t)p.batch * p.n_kv_heads * p.head_groups
+                                                        : ((int64_t)p.batch * p.n_kv_heads) << HSHIFT;
     const int64_t total_a = units * p.plan.n_splits_a, total_b = units * p.plan.n_splits_b;
     // Cost of an fp16-row chunk in units of an all-quantised chunk: by the bytes they stream, times
     // a measured factor per instantiation -- with 5 to 8 query heads per kv-head, and with 3 or 4 at
@@ -1515,6 +1525,15 @@ bool with_variant(int bits, int rep_layout, F&& fn) {
 
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
+    if (p.head_groups > 1) {
+        // runs of 8 query heads of every kv-head as units of one single-form launch
+        if (p.two_launches > 0 || p.head_split > 0 || p.q_head0 != 0 || p.rep_here != kMaxRep || p.rep_variant != kMaxRep ||
+            p.seq_state != nullptr || p.head_groups != (p.n_q_heads / p.n_kv_heads + kMaxRep - 1) / kMaxRep)
+            return hipErrorInvalidValue;
+        if (p.bits == 2) return launch_one<2, 8, 4, 2, kRuntimeHeadGroups>(p, stream);
+        if (p.bits == 4) return launch_one<4, 8, 2, 2, kRuntimeHeadGroups>(p, stream);
+        return hipErrorNotSupported;
+    }
     if (p.head_split > 0) {
         // 2^head_split equal parts of every kv-head's query heads as units of their own, on the
         // instantiation for one part
