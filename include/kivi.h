@@ -94,9 +94,9 @@ typedef struct kivi_layout {
     int32_t batch;          /* b                                                          */
     int32_t n_q_heads;      /* query heads; a multiple (1x to 128x) of n_kv_heads: up to  */
                             /* 8 query heads per kv-head share one pass over the cache,   */
-                            /* wider groups (multi-query attention) take one pass per 8:  */
-                            /* as units of one launch in the matrix-core family's single- */
-                            /* launch form, as launches of their own otherwise            */
+                            /* wider groups (multi-query attention) run as units of one   */
+                            /* launch (runs of 4 heads) in the matrix-core family's       */
+                            /* single-launch form, one launch per 8 heads otherwise       */
     int32_t n_kv_heads;     /* key/value heads                                            */
     int32_t head_dim;       /* D; this build supports 128                                 */
     int32_t bits;           /* B: 2 or 4                                                  */
@@ -143,9 +143,9 @@ typedef struct kivi_decode_plan {
     int32_t tiles_per_split_quantised, tiles_per_split_fp16;   /* in 32-token tiles                */
     int32_t units_per_kv_head;  /* 1; 2 or 4 when the query heads of every kv-head are served as    */
                                 /* halves or quarters that read the cache independently (4, 6 or 8  */
-                                /* heads per kv-head, small batches); ceil(heads per kv-head / 8)   */
+                                /* heads per kv-head, small batches); ceil(heads per kv-head / 4)   */
                                 /* when a wider group (multi-query attention) runs as ONE launch    */
-                                /* whose units are runs of 8 query heads                            */
+                                /* whose units are runs of 4 query heads                            */
 } kivi_decode_plan_t;
 
 /* Host helper: the plan for `cache`'s current state (no launch).  Errors: INVALID_ARG, UNSUPPORTED. */

@@ -1526,12 +1526,14 @@ bool with_variant(int bits, int rep_layout, F&& fn) {
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
     if (p.head_groups > 1) {
-        // runs of 8 query heads of every kv-head as units of one single-form launch
-        if (p.two_launches > 0 || p.head_split > 0 || p.q_head0 != 0 || p.rep_here != kMaxRep || p.rep_variant != kMaxRep ||
-            p.seq_state != nullptr || p.head_groups != (p.n_q_heads / p.n_kv_heads + kMaxRep - 1) / kMaxRep)
+        // runs of 4 (or 8) query heads of every kv-head as units of one single-form launch
+        if (p.two_launches > 0 || p.head_split > 0 || p.q_head0 != 0 || (p.rep_here != 4 && p.rep_here != 8) || p.rep_variant != p.rep_here ||
+            p.seq_state != nullptr || p.head_groups != (p.n_q_heads / p.n_kv_heads + p.rep_here - 1) / p.rep_here)
             return hipErrorInvalidValue;
-        if (p.bits == 2) return launch_one<2, 8, 4, 2, kRuntimeHeadGroups>(p, stream);
-        if (p.bits == 4) return launch_one<4, 8, 2, 2, kRuntimeHeadGroups>(p, stream);
+        if (p.bits == 2 && p.rep_here == 8) return launch_one<2, 8, 4, 2, kRuntimeHeadGroups>(p, stream);
+        if (p.bits == 4 && p.rep_here == 8) return launch_one<4, 8, 2, 2, kRuntimeHeadGroups>(p, stream);
+        if (p.bits == 2 && p.rep_here == 4) return launch_one<2, 4, 4, 2, kRuntimeHeadGroups>(p, stream);
+        if (p.bits == 4 && p.rep_here == 4) return launch_one<4, 4, 2, 2, kRuntimeHeadGroups>(p, stream);
         return hipErrorNotSupported;
     }
     if (p.head_split > 0) {

@@ -111,7 +111,7 @@ struct DecodeParams {
     // and the plan above then describe the LONGEST sequence: every unit gets that many chunks on the
     // cost axis, and a shorter sequence's surplus chunks and tiles are masked.
     const int32_t* seq_state;
-    int32_t head_groups;        // > 1: runs of kMaxRep query heads per kv-head served as units of one launch (matrix-core family)
+    int32_t head_groups;        // > 1: runs of rep_here (4 or 8) query heads per kv-head served as units of one launch (matrix-core family)
     int32_t ragged_min_tiles;   // with seq_state: the fewest all-quantised tiles any sequence has (host knowledge)
     // Host side only (two-launch form): the residual flush of this decode step, to be carried out by
     // extra workgroups of the fp16-row launch instead of a launch of its own; null otherwise.

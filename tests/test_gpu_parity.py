@@ -92,10 +92,10 @@ def test_many_units_one_per_wavefront(bits, rep, batch, n_kv, length):
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("n_kv,rep", [(2, 9), (2, 16), (1, 71)])
 def test_wide_groups(path, bits, n_kv, rep):
-    """More than 8 query heads per kv-head: runs of 8 heads (9 = 8 + 1, 16 = two full runs, 71 heads
-    on a single kv-head = the multi-query shape of Falcon-7B, 8 runs of 8 and one of 7) -- units of
-    one launch in the matrix-core family's single-launch form, launches of their own in the forced
-    two-launch form and in the vector-ALU family."""
+    """More than 8 query heads per kv-head (9, 16, and 71 heads on a single kv-head = the multi-query
+    shape of Falcon-7B): runs of 4 heads as units of one launch in the matrix-core family's
+    single-launch form (the last run shorter: 9 = 4 + 4 + 1, 71 = 17 x 4 + 3), one launch per 8 heads
+    in the forced two-launch form and in the vector-ALU family."""
     w = scaled(CONFIGS["mistral_gqa"], name="wide", batch=2, n_q_heads=n_kv * rep, n_kv_heads=n_kv, bits=bits,
                seed=1500 + rep + bits)
     print(f"case wide path={path} bits={bits} kv={n_kv} rep={rep}", flush=True)
