@@ -31,15 +31,13 @@
  *
  * Memory layout (all arrays dense, index order as written, b = batch entry, h = kv-head)
  *   k_codes  uint32 [b][h][cap_q/32][W]   one "key tile" per block of 32 tokens, W = 32*128*B/32
- *   k_scale  fp16   [b][h][cap_q/32][128]  per (tile, channel)
- *   k_zero   fp16   [b][h][cap_q/32][128]
+ *   k_scale  fp16   [b][h][cap_q/G][128]   per (group of G tokens, channel)
+ *   k_zero   fp16   [b][h][cap_q/G][128]
  *   v_codes  uint32 [b][h][cap_q/32][W]   one "value tile" per block of 32 tokens
- *   v_scale  fp16   [b][h][cap_q][4]       per (token, block of 32 channels)
- *   v_zero   fp16   [b][h][cap_q][4]
- *   Scales and zero-points are kept at this 32-token / 32-channel granularity for every G: with
- *   G = 64 or 128 a group's pair is stored in each of the G/32 tiles (blocks) it covers, so the
- *   decode kernels read the same arrays whatever G is (the scale bytes a larger G would save are
- *   not saved).
+ *   v_scale  fp16   [b][h][cap_q][128/G]   per (token, group of G channels)
+ *   v_zero   fp16   [b][h][cap_q][128/G]
+ *   One scale / zero-point pair per group, whatever G is (32, 64 or 128): a larger G stores, and the
+ *   decode kernels read, proportionally fewer of them (Table 5 / Appendix C's group sizes).
  *   k_resid  fp16   [b][h][cap_r][128]     ring buffer: the i-th oldest residual token is in slot
  *   v_resid  fp16   [b][h][cap_r][128]     (r_start + i) % cap_r
  *   q        fp16   [b][n_q_heads][128]

@@ -272,6 +272,7 @@ bool wants_two_launches(const kivi_layout_t* l, const kivi_cache_t* c, int path)
 int head_split_shift(const kivi_layout_t* l, const SplitPlan& plan, int path, bool two_launches) {
     const int rep_total = l->n_q_heads / l->n_kv_heads;
     if (path != KIVI_DECODE_MFMA || two_launches || (rep_total != 4 && rep_total != 6 && rep_total != 8)) return 0;
+    if (l->group != kTileTokens) return 0;            // G > 32 runs on instantiations of its own, which exist for whole groups only
     const int64_t units = (int64_t)l->batch * l->n_kv_heads, chunks = units * plan.n_splits();
     // parts of 2 heads run on the 2-head instantiation: 2 bits only (at 4 bits that instantiation's
     // chunks are not the length the plan was made for)
@@ -294,7 +295,7 @@ constexpr int kWideGroupRun = 4;
 int wide_group_width(const kivi_layout_t*) { return kWideGroupRun; }
 int wide_group_runs(const kivi_layout_t* l, int path, bool two_launches) {
     const int rep_total = l->n_q_heads / l->n_kv_heads;
-    if (path != KIVI_DECODE_MFMA || two_launches || rep_total <= kMaxRep) return 1;
+    if (path != KIVI_DECODE_MFMA || two_launches || rep_total <= kMaxRep || l->group != kTileTokens) return 1;
     return ceil_div(rep_total, wide_group_width(l));
 }
 
@@ -321,6 +322,7 @@ int enqueue_attention(const kivi_layout_t* l, const kivi_cache_t* c, const void*
     p.q = static_cast<const __half*>(q); p.out = out;
     p.softmax_scale = softmax_scale;
     p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
+    p.kg_shift = l->group == 32 ? 0 : (l->group == 64 ? 1 : 2);
     p.length = length;
     const int path = decode_family(l);
     if ((k_new || v_new) && path != KIVI_DECODE_MFMA) return KIVI_ERR_UNSUPPORTED;
@@ -423,7 +425,7 @@ int ragged_attention_fast(const kivi_layout_t* l, const kivi_cache_t* c, const k
                           float softmax_scale, float* out, void* workspace, size_t workspace_bytes,
                           const void* k_new, const void* v_new, void* stream) {
     if (decode_family(l) != KIVI_DECODE_MFMA || l->decode_path == KIVI_DECODE_MFMA_ONE) return kNotApplicable;
-    if (l->cap_q_tokens < kTileTokens) return kNotApplicable;
+    if (l->cap_q_tokens < kTileTokens || l->group != kTileTokens) return kNotApplicable;
     const int rep_total = l->n_q_heads / l->n_kv_heads;
     const int rep_launch = std::min(rep_total, kMaxRep);
     const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
@@ -458,6 +460,7 @@ int ragged_attention_fast(const kivi_layout_t* l, const kivi_cache_t* c, const k
     p.q = static_cast<const __half*>(q); p.out = out;
     p.softmax_scale = softmax_scale;
     p.batch = l->batch; p.n_q_heads = l->n_q_heads; p.n_kv_heads = l->n_kv_heads; p.bits = l->bits;
+    p.kg_shift = l->group == 32 ? 0 : (l->group == 64 ? 1 : 2);
     p.plan.tiles_a = max_tiles_a;
     p.plan.tiles_total = max_tiles_a + max_tiles_b;
     p.plan.tiles_per_split_a = g.chunk_tiles;
@@ -536,7 +539,7 @@ int ragged_step_fast(const kivi_layout_t* l, const kivi_cache_t* c, kivi_seq_sta
     {
         const int rep_launch = std::min(l->n_q_heads / l->n_kv_heads, kMaxRep);
         const int rep_variant = rep_launch <= 2 ? rep_launch : (rep_launch <= 4 ? 4 : 8);
-        if (l->decode_path == KIVI_DECODE_MFMA_ONE || l->cap_q_tokens < kTileTokens) return kNotApplicable;
+        if (l->decode_path == KIVI_DECODE_MFMA_ONE || l->cap_q_tokens < kTileTokens || l->group != kTileTokens) return kNotApplicable;
         int max_tiles_a = 0, max_tiles_b = 0;
         for (int b = 0; b < l->batch; ++b) {
             const kivi_seq_state_t& x = after[b];
@@ -621,8 +624,9 @@ int kivi_cache_sizes(const kivi_layout_t* l, kivi_cache_sizes_t* out) {
     const size_t tiles = (size_t)l->cap_q_tokens / kTileTokens;
     const size_t words = (size_t)kTileTokens * kHeadDim * l->bits / 32;
     out->k_codes = out->v_codes = units * tiles * words * 4;
-    out->k_scale = out->k_zero = units * tiles * kHeadDim * 2;
-    out->v_scale = out->v_zero = units * (size_t)l->cap_q_tokens * (kHeadDim / kTileTokens) * 2;
+    // one scale / zero-point per group: keys per (G tokens, channel), values per (token, G channels)
+    out->k_scale = out->k_zero = units * ((size_t)l->cap_q_tokens / l->group) * kHeadDim * 2;
+    out->v_scale = out->v_zero = units * (size_t)l->cap_q_tokens * (kHeadDim / l->group) * 2;
     out->k_resid = out->v_resid = units * (size_t)l->cap_r_tokens * kHeadDim * 2;
     return KIVI_OK;
 }
@@ -885,7 +889,8 @@ int kivi_decode_launches_ragged(const kivi_layout_t* l, const kivi_seq_state_t* 
     const int rep_total = l->n_q_heads / l->n_kv_heads;
     const int head_groups = ceil_div(rep_total, kMaxRep);
     // the conditions of ragged_attention_fast
-    bool fast = path == KIVI_DECODE_MFMA && l->decode_path != KIVI_DECODE_MFMA_ONE && l->cap_q_tokens >= kTileTokens;
+    bool fast = path == KIVI_DECODE_MFMA && l->decode_path != KIVI_DECODE_MFMA_ONE && l->cap_q_tokens >= kTileTokens &&
+                l->group == kTileTokens;
     int max_tiles_a = 0, max_tiles_b = 0;
     for (int b = 0; b < l->batch; ++b) {
         const kivi_seq_state_t& x = states[b];

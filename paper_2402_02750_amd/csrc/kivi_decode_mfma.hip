@@ -152,6 +152,39 @@ __device__ __forceinline__ __half2 nt_half2(const __half* p) {
     return r.h;
 }
 
+// Scales (or zero-points) of the two channel groups a lane stages for the value side: lane l takes
+// token l / 2 of a tile and the 32-channel blocks 2 (l % 2) and 2 (l % 2) + 1.  The array holds
+// 4 >> kg entries per token (one per group of G = 32 << kg channels): with G = 32 the pair is one
+// aligned 4-byte word; with G = 64 / 128 both blocks share the entry at half-word
+// ((tile * 128 + 2 l) >> kg), so the aligned word that holds it is loaded and, when the data is
+// consumed (nothing may touch a requested word earlier: that would wait for the load), the entry is
+// copied into both halves by one byte permute with a lane-constant selector.  Only the instantiations
+// for G > 32 (CS) carry this; with G = 32 it all folds away.
+struct ValueScaleLane {
+    int off;            // lane's part of the word offset, in halves (even)
+    uint32_t sel;       // byte-permute selector: "low half twice" / "high half twice"
+};
+template <bool CS>
+__device__ __forceinline__ ValueScaleLane value_scale_lane(int lane, int kg) {
+    ValueScaleLane v;
+    const int h = CS ? (2 * lane) >> kg : 2 * lane;
+    v.off = CS ? h & ~1 : h;
+    v.sel = (h & 1) ? 0x03020302u : 0x01000100u;
+    return v;
+}
+template <bool CS>
+__device__ __forceinline__ __half2 value_scale_word(const __half* base, int64_t tile, int kg, ValueScaleLane v) {
+    return nt_half2(base + (CS ? (tile * (kTileTokens * 4)) >> kg : tile * (kTileTokens * 4)) + v.off);
+}
+template <bool CS>
+__device__ __forceinline__ __half2 value_scale_pair(__half2 word, ValueScaleLane v) {
+    if constexpr (!CS) return word;
+    union { uint32_t u; __half2 h; } a, r;
+    a.h = word;
+    r.u = __builtin_amdgcn_perm(a.u, a.u, v.sel);
+    return r.h;
+}
+
 template <int BITS>
 __device__ __forceinline__ void load_tile_words(const uint32_t* tile, int lane, uint32_t* w) {
     constexpr int kPlanes = BITS / 2;
@@ -296,7 +329,7 @@ __device__ __forceinline__ void value_tile_mfma(const uint32_t* w, const __half*
 constexpr int kBothPhases = 0, kQuantisedOnly = 1, kQuantisedRagged = 2;
 constexpr int kRuntimeHeadGroups = 15;      // value of HSHIFT: the number of head runs per kv-head is a launch parameter
 
-template <int BITS, int REP, int SLOTS, int OCC, int MODE, int HSHIFT = 0>
+template <int BITS, int REP, int SLOTS, int OCC, int MODE, int HSHIFT = 0, bool CS = false>
 __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     constexpr bool kQOnly = MODE != kBothPhases, kRagged = MODE == kQuantisedRagged;
     constexpr int kSlots = SLOTS;
@@ -331,6 +364,9 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
     constexpr int kWords = kTileTokens * kHeadDim * BITS / 32;
     constexpr int kLaneWords = BITS * 2;
     WL& wl = sm_w[wave];
+    // CS: scales and zero-points stored once per group of G = 32 << kg tokens (keys) / channels (values), G > 32
+    const int kg = CS ? p.kg_shift : 0;
+    const ValueScaleLane vlane = CS ? value_scale_lane<CS>(lane, kg) : ValueScaleLane{0, 0u};
 
     // REP is the instantiation's head count; the layout may have fewer query heads per kv-head
     // (3, 5, 6, 7): the surplus heads run on a zero query and are never stored
@@ -429,26 +465,41 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
         const int t = min(wave + 4 * slot_or_row, nx_nt - 1);
         return nx_base + (kRagged ? max(t, 0) : t);
     };
+    // row of the key scale / zero-point arrays (one per group of G = 32 << kg tokens) of that tile:
+    // the chunk's first tile is a multiple of G / 32, so base and offset can be shifted apart (the
+    // offset may differ from lane to lane: a 32-bit shift instead of a 64-bit one)
+    auto chunk_key_row = [&](int slot_or_row) -> int64_t {
+        const int t = min(wave + 4 * slot_or_row, nx_nt - 1);
+        return (nx_base >> kg) + ((kRagged ? max(t, 0) : t) >> kg);
+    };
     // Requests for the "next" all-quantised chunk.  They are issued unconditionally so that the
     // compiler can count outstanding loads exactly (a conditional load forces a wait for *all*
     // outstanding loads at the next use); when there is no next chunk they read tile 0 of unit 0,
     // which stays in L2, and the result is never used.
     auto request_zero_rows = [&]() {
-        const int64_t tile = nx_ok ? chunk_tile(min(n, kSlots - 1)) : 0;   // A row n = slot n
+        int64_t row;                                                         // A row n = slot n
+        if constexpr (CS) row = nx_ok ? chunk_key_row(min(n, kSlots - 1)) : 0;
+        else row = nx_ok ? chunk_tile(min(n, kSlots - 1)) : 0;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            zf[ks] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8));
+            zf[ks] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(p.k_zero + row * kHeadDim + ks * 32 + rq * 8));
     };
     auto request_key_slot = [&](int i) {
         const int64_t tile = nx_ok ? chunk_tile(i) : 0;
         load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
-        ks2[i] = nt_half2(p.k_scale + tile * kHeadDim + 2 * lane);
+        if constexpr (CS) ks2[i] = nt_half2(p.k_scale + (nx_ok ? chunk_key_row(i) : 0) * kHeadDim + 2 * lane);
+        else ks2[i] = nt_half2(p.k_scale + tile * kHeadDim + 2 * lane);
     };
     auto request_value_slot = [&](int i) {
         const int64_t tile = nx_ok ? chunk_tile(i) : 0;
         load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
-        vs2[i] = nt_half2(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
-        vz2[i] = nt_half2(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+        if constexpr (CS) {
+            vs2[i] = value_scale_word<CS>(p.v_scale, tile, kg, vlane);
+            vz2[i] = value_scale_word<CS>(p.v_zero, tile, kg, vlane);
+        } else {
+            vs2[i] = nt_half2(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
+            vz2[i] = nt_half2(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+        }
     };
 
     // per-wave running state of the current unit
@@ -848,7 +899,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             int cnt_kq = 0;
             for (int i = 0; i < cnt; ++i) cnt_kq += ((tile0 + wave + 4 * i) * kTileTokens < p.n_kq) ? 1 : 0;
             if (cnt_kq > 0) {
-                const __half* zrow = p.k_zero + (ubase + wave + 4 * min(n, cnt_kq - 1)) * kHeadDim;
+                const __half* zrow = p.k_zero + ((ubase + wave + 4 * min(n, cnt_kq - 1)) >> kg) * kHeadDim;
                 float4v d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
@@ -904,7 +955,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                     uint32_t w[kLaneWords];
                     load_tile_words<BITS>(p.k_codes + (ubase + wave + 4 * i) * kWords, lane, w);
                     const __half2 s2 = *reinterpret_cast<const __half2*>(
-                        p.k_scale + (ubase + wave + 4 * i) * kHeadDim + 2 * lane);
+                        p.k_scale + ((ubase + wave + 4 * i) >> kg) * kHeadDim + 2 * lane);
                     stage_key_operand<REP>(wl.b, s2, qpf, lane);
                     wave_lds_sync();
                     key_tile_mfma<BITS, REP>(w, wl.b, wl.lr, i, lane);
@@ -967,9 +1018,15 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
                 if (n_vq_here > 0 && h0 == 0) {
                     uint32_t w[kLaneWords];
                     load_tile_words<BITS>(p.v_codes + (ubase + wave + 4 * i) * kWords, lane, w);
-                    const int64_t so = (ubase + wave + 4 * i) * kTileTokens * 4 + 2 * lane;
-                    const __half2 s2 = *reinterpret_cast<const __half2*>(p.v_scale + so);
-                    const __half2 z2 = *reinterpret_cast<const __half2*>(p.v_zero + so);
+                    __half2 s2, z2;
+                    if constexpr (CS) {
+                        s2 = value_scale_pair<CS>(value_scale_word<CS>(p.v_scale, ubase + wave + 4 * i, kg, vlane), vlane);
+                        z2 = value_scale_pair<CS>(value_scale_word<CS>(p.v_zero, ubase + wave + 4 * i, kg, vlane), vlane);
+                    } else {
+                        const int64_t so = (ubase + wave + 4 * i) * kTileTokens * 4 + 2 * lane;
+                        s2 = *reinterpret_cast<const __half2*>(p.v_scale + so);
+                        z2 = *reinterpret_cast<const __half2*>(p.v_zero + so);
+                    }
                     stage_value_operand<BITS, REP, true>(wl.b, s2, z2, n_vq_here, wl.lr, i, zacc, lane);
                     wave_lds_sync();
                     value_tile_mfma<BITS, REP>(w, wl.b, acc, lane);
@@ -1104,7 +1161,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
             for (int c0 = 0; c0 < kSlots; c0 += SS) {
 #pragma unroll
                 for (int s = 0; s < SS; ++s)
-                    stage_value_operand<BITS, REP, false>(wl.b + s * WL::kVSlot, vs2[c0 + s], vz2[c0 + s],
+                    stage_value_operand<BITS, REP, false>(wl.b + s * WL::kVSlot, value_scale_pair<CS>(vs2[c0 + s], vlane), value_scale_pair<CS>(vz2[c0 + s], vlane),
                                                           kTileTokens, wl.lr, c0 + s, zacc, lane);
                 wave_lds_sync();
 #pragma unroll
@@ -1127,7 +1184,7 @@ __global__ __launch_bounds__(256, OCC) void decode_mfma_kernel(DecodeParams p) {
 // answer is kept per device (the only state the library keeps; a plain integer per device and
 // instantiation, written once with the same value by whichever thread asks first).
 constexpr int kMaxDevices = 64;
-template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases, int HSHIFT = 0>
+template <int BITS, int REP, int SLOTS, int OCC, int MODE = kBothPhases, int HSHIFT = 0, bool CS = false>
 int resident_workgroups() {
     static std::atomic<int> cached[kMaxDevices];
     int dev = 0, cus = 0, per_cu = 0;
@@ -1138,7 +1195,7 @@ int resident_workgroups() {
         if (c > 0) return c;
     }
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE, HSHIFT>, 256, 0) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_mfma_kernel<BITS, REP, SLOTS, OCC, MODE, HSHIFT, CS>, 256, 0) != hipSuccess ||
         cus <= 0 || per_cu <= 0)
         return 256 * OCC;
     if (keep) cached[dev].store(cus * per_cu, std::memory_order_relaxed);
@@ -1157,7 +1214,7 @@ int resident_workgroups() {
 // unit ahead): no barrier, no cross-wavefront merge, no device-scope traffic; leaving a unit is
 // a reduction inside the wavefront and the output store.  Same tile arithmetic (the device functions
 // above), same running-maximum softmax, same merge with the part of the fp16-row launch.
-template <int BITS, int REP, int OCC>
+template <int BITS, int REP, int OCC, bool CS = false>
 __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParams p) {
     constexpr int kSlots = 4;
     constexpr int kStage = REP > 2 ? 1 : 2;
@@ -1175,6 +1232,8 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int n = lane & 15, rq = lane >> 4, ncol = n & (NC - 1);
     WL& wl = sm_w[wave];
+    const int kg = CS ? p.kg_shift : 0;
+    const ValueScaleLane vlane = CS ? value_scale_lane<CS>(lane, kg) : ValueScaleLane{0, 0u};
     const int rep = p.rep_here, rep_total = p.n_q_heads / p.n_kv_heads;
     const int units = p.batch * p.n_kv_heads;
     const int n_waves = (int)gridDim.x * 4, gw = (int)blockIdx.x * 4 + wave;
@@ -1199,6 +1258,10 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
     auto next_tile = [&](int slot) -> int64_t {
         return nx_ok ? (int64_t)nx_u * p.cap_tiles + min(nx_g * kSlots + slot, nx_tiles - 1) : 0;
     };
+    // row of the key scale / zero-point arrays (one per group of G = 32 << kg tokens) of that tile
+    auto next_key_row = [&](int slot) -> int64_t {
+        return nx_ok ? (((int64_t)nx_u * p.cap_tiles) >> kg) + (min(nx_g * kSlots + slot, nx_tiles - 1) >> kg) : 0;
+    };
     auto advance_next = [&]() {
         if (++nx_g * kSlots >= nx_tiles) {
             nx_g = 0;
@@ -1208,21 +1271,29 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
         }
     };
     auto request_zero_rows = [&]() {
-        const int64_t tile = next_tile(min(n, kSlots - 1));                // A row n = slot n
+        int64_t row;                                                       // A row n = slot n
+        if constexpr (CS) row = next_key_row(min(n, kSlots - 1));
+        else row = next_tile(min(n, kSlots - 1));
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
-            zf[ks] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(p.k_zero + tile * kHeadDim + ks * 32 + rq * 8));
+            zf[ks] = __builtin_nontemporal_load(reinterpret_cast<const half8*>(p.k_zero + row * kHeadDim + ks * 32 + rq * 8));
     };
     auto request_key_slot = [&](int i) {
         const int64_t tile = next_tile(i);
         load_tile_words<BITS>(p.k_codes + tile * kWords, lane, kw[i]);
-        ks2[i] = nt_half2(p.k_scale + tile * kHeadDim + 2 * lane);
+        if constexpr (CS) ks2[i] = nt_half2(p.k_scale + next_key_row(i) * kHeadDim + 2 * lane);
+        else ks2[i] = nt_half2(p.k_scale + tile * kHeadDim + 2 * lane);
     };
     auto request_value_slot = [&](int i) {
         const int64_t tile = next_tile(i);
         load_tile_words<BITS>(p.v_codes + tile * kWords, lane, vw[i]);
-        vs2[i] = nt_half2(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
-        vz2[i] = nt_half2(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+        if constexpr (CS) {
+            vs2[i] = value_scale_word<CS>(p.v_scale, tile, kg, vlane);
+            vz2[i] = value_scale_word<CS>(p.v_zero, tile, kg, vlane);
+        } else {
+            vs2[i] = nt_half2(p.v_scale + tile * kTileTokens * 4 + 2 * lane);
+            vz2[i] = nt_half2(p.v_zero + tile * kTileTokens * 4 + 2 * lane);
+        }
     };
     // query and fp16-row part of a unit: lane l holds the elements (head k / 2, channel l + 64 (k % 2))
     __half q_pre[kIdx];
@@ -1357,7 +1428,7 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
             for (int c0 = 0; c0 < kSlots; c0 += SS) {
 #pragma unroll
                 for (int sl = 0; sl < SS; ++sl)
-                    stage_value_operand<BITS, REP, false>(wl.b + sl * WL::kVSlot, vs2[c0 + sl], vz2[c0 + sl],
+                    stage_value_operand<BITS, REP, false>(wl.b + sl * WL::kVSlot, value_scale_pair<CS>(vs2[c0 + sl], vlane), value_scale_pair<CS>(vz2[c0 + sl], vlane),
                                                           kTileTokens, wl.lr, c0 + sl, zacc, lane);
                 wave_lds_sync();
 #pragma unroll
@@ -1411,7 +1482,7 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
 }
 
 // Wavefronts the device holds at once for decode_wave_units_kernel (per device, as above).
-template <int BITS, int REP, int OCC>
+template <int BITS, int REP, int OCC, bool CS = false>
 int resident_wave_unit_workgroups() {
     static std::atomic<int> cached[kMaxDevices];
     int dev = 0, cus = 0, per_cu = 0;
@@ -1422,14 +1493,14 @@ int resident_wave_unit_workgroups() {
         if (c > 0) return c;
     }
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_wave_units_kernel<BITS, REP, OCC>, 256, 0) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_wave_units_kernel<BITS, REP, OCC, CS>, 256, 0) != hipSuccess ||
         cus <= 0 || per_cu <= 0)
         return 256 * OCC;
     if (keep) cached[dev].store(cus * per_cu, std::memory_order_relaxed);
     return cus * per_cu;
 }
 
-template <int BITS, int REP, int SLOTS, int OCC, int HSHIFT = 0>
+template <int BITS, int REP, int SLOTS, int OCC, int HSHIFT = 0, bool CS = false>
 hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.tiles_per_split_b > kMfmaSplitTiles) return hipErrorInvalidValue;
     const int64_t units = HSHIFT == kRuntimeHeadGroups ? (int64_t)p.batch * p.n_kv_heads * p.head_groups
@@ -1452,15 +1523,15 @@ hipError_t launch_one(DecodeParams p, hipStream_t stream) {
     p.total_chunks_a = (int)total_a;
     p.total_chunks_b = (int)total_b;
     // every resident workgroup gets an equal share of the cost axis (within one unit of cost)
-    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kBothPhases, HSHIFT>(),
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kBothPhases, HSHIFT, CS>(),
                                                                   p.total_cost / p.cost_b));
-    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kBothPhases, HSHIFT><<<grid, 256, 0, stream>>>(p);
+    decode_mfma_kernel<BITS, REP, SLOTS, OCC, kBothPhases, HSHIFT, CS><<<grid, 256, 0, stream>>>(p);
     return hipGetLastError();
 }
 
 // The two-launch form: the fp16 rows of all units (residual_rows_kernel), then the all-quantised
 // chunks on a cost axis of their own (unit-major, one unit of cost per chunk).
-template <int BITS, int REP, int SLOTS, int OCC>
+template <int BITS, int REP, int SLOTS, int OCC, bool CS = false>
 hipError_t launch_two(DecodeParams p, hipStream_t stream) {
     if (p.plan.tiles_per_split_a != 4 * SLOTS || p.plan.n_splits_a < 1) return hipErrorInvalidValue;
     const int64_t units = (int64_t)p.batch * p.n_kv_heads;
@@ -1481,22 +1552,26 @@ hipError_t launch_two(DecodeParams p, hipStream_t stream) {
     // One unit per wavefront where that fills the chip evenly: at least as many units as resident
     // wavefronts, and the last round of units at most 12 % short of a full one.
     if constexpr (REP <= 4) {
-        if (!p.seq_state || p.ragged_min_tiles >= 1) {
-            const int64_t waves = 4 * (int64_t)resident_wave_unit_workgroups<BITS, REP, OCC>();
+        if (!p.seq_state || (!CS && p.ragged_min_tiles >= 1)) {
+            const int64_t waves = 4 * (int64_t)resident_wave_unit_workgroups<BITS, REP, OCC, CS>();
             const int64_t rounds = (units + waves - 1) / waves;
             if (units >= waves && rounds * waves * 100 <= units * 112 && p.plan.tiles_a >= 1 && p.plan.n_splits_b == 1) {
                 const int grid = (int)std::min<int64_t>(waves / 4, (units + 3) / 4);
-                decode_wave_units_kernel<BITS, REP, OCC><<<grid, 256, 0, stream>>>(p);
+                decode_wave_units_kernel<BITS, REP, OCC, CS><<<grid, 256, 0, stream>>>(p);
                 return hipGetLastError();
             }
         }
     }
     if (p.seq_state) {
-        const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedRagged>(), total_a);
-        decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedRagged><<<grid, 256, 0, stream>>>(p);
+        if constexpr (CS) {
+            return hipErrorNotSupported;        // batches of different lengths with G > 32 go run by run (the host does not send them here)
+        } else {
+            const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedRagged>(), total_a);
+            decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedRagged><<<grid, 256, 0, stream>>>(p);
+        }
     } else {
-        const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedOnly>(), total_a);
-        decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedOnly><<<grid, 256, 0, stream>>>(p);
+        const int grid = (int)std::min<int64_t>(resident_workgroups<BITS, REP, SLOTS, OCC, kQuantisedOnly, 0, CS>(), total_a);
+        decode_mfma_kernel<BITS, REP, SLOTS, OCC, kQuantisedOnly, 0, CS><<<grid, 256, 0, stream>>>(p);
     }
     return hipGetLastError();
 }
@@ -1525,6 +1600,7 @@ bool with_variant(int bits, int rep_layout, F&& fn) {
 
 hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
     hipError_t e = hipErrorNotSupported;
+    if ((p.head_groups > 1 || p.head_split > 0) && p.kg_shift > 0) return hipErrorNotSupported;   // G > 32: whole groups, one pass per 8 heads
     if (p.head_groups > 1) {
         // runs of 4 (or 8) query heads of every kv-head as units of one single-form launch
         if (p.two_launches > 0 || p.head_split > 0 || p.q_head0 != 0 || (p.rep_here != 4 && p.rep_here != 8) || p.rep_variant != p.rep_here ||
@@ -1547,6 +1623,15 @@ hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
         if (p.head_split == 1 && p.bits == 2 && p.rep_variant == 2) return launch_one<2, 2, 4, 2, 1>(p, stream);
         if (p.head_split == 2 && p.bits == 2 && p.rep_variant == 2) return launch_one<2, 2, 4, 2, 2>(p, stream);
         return hipErrorNotSupported;
+    }
+    if (p.kg_shift > 0) {
+        // G = 64 / 128: the instantiations that read one scale / zero-point pair per group
+        with_variant(p.bits, p.rep_variant, [&](auto v) {
+            using V = decltype(v);
+            e = p.two_launches > 0 ? launch_two<V::bits, V::rep, V::slots, V::occ, true>(p, stream)
+                                   : launch_one<V::bits, V::rep, V::slots, V::occ, 0, true>(p, stream);
+        });
+        return e;
     }
     with_variant(p.bits, p.rep_variant, [&](auto v) {
         using V = decltype(v);

@@ -109,8 +109,8 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
             const int r = lane & 15, kq = lane >> 4;
             uint32_t w[kLaneWords];
             load_tile_words<BITS>(p.k_codes + (unit * p.cap_tiles + tile) * kWords, lane, w);
-            const __half* sc = p.k_scale + (unit * p.cap_tiles + tile) * kHeadDim;
-            const __half* zr = p.k_zero + (unit * p.cap_tiles + tile) * kHeadDim;
+            const __half* sc = p.k_scale + ((unit * p.cap_tiles + tile) >> p.kg_shift) * kHeadDim;
+            const __half* zr = p.k_zero + ((unit * p.cap_tiles + tile) >> p.kg_shift) * kHeadDim;
             float acc0[REP], acc1[REP];
 #pragma unroll
             for (int hh = 0; hh < REP; ++hh) acc0[hh] = acc1[hh] = 0.f;
@@ -235,16 +235,29 @@ __global__ __launch_bounds__(256) void decode_valu_kernel(DecodeParams p) {
             load_tile_words<BITS>(p.v_codes + (unit * p.cap_tiles + tile) * kWords, lane, w);
             const int64_t tok = (unit * p.cap_tiles + tile) * kTileTokens + kq * 8;
             float s[8][4], z[8][4];
+            if (p.kg_shift == 0) {
 #pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {      // 2 tokens (8 halves) per 16-byte load
-                float fs[8], fz[8];
-                unpack8(*reinterpret_cast<const Half8*>(p.v_scale + (tok + e2 * 2) * 4), fs);
-                unpack8(*reinterpret_cast<const Half8*>(p.v_zero + (tok + e2 * 2) * 4), fz);
+                for (int e2 = 0; e2 < 4; ++e2) {      // 2 tokens (8 halves) per 16-byte load
+                    float fs[8], fz[8];
+                    unpack8(*reinterpret_cast<const Half8*>(p.v_scale + (tok + e2 * 2) * 4), fs);
+                    unpack8(*reinterpret_cast<const Half8*>(p.v_zero + (tok + e2 * 2) * 4), fz);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    s[e2 * 2][i] = fs[i]; s[e2 * 2 + 1][i] = fs[4 + i];
-                    z[e2 * 2][i] = fz[i]; z[e2 * 2 + 1][i] = fz[4 + i];
+                    for (int i = 0; i < 4; ++i) {
+                        s[e2 * 2][i] = fs[i]; s[e2 * 2 + 1][i] = fs[4 + i];
+                        z[e2 * 2][i] = fz[i]; z[e2 * 2 + 1][i] = fz[4 + i];
+                    }
                 }
+            } else {
+                // G = 64 / 128: 2 or 1 entries per token, shared by 2 or 4 of the 32-channel blocks
+                const int per_token = 4 >> p.kg_shift;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int64_t o = (tok + e) * per_token + (i >> p.kg_shift);
+                        s[e][i] = __half2float(p.v_scale[o]);
+                        z[e][i] = __half2float(p.v_zero[o]);
+                    }
             }
 #pragma unroll
             for (int hh = 0; hh < REP; ++hh) {

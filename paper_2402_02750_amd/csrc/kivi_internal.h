@@ -111,6 +111,8 @@ struct DecodeParams {
     // and the plan above then describe the LONGEST sequence: every unit gets that many chunks on the
     // cost axis, and a shorter sequence's surplus chunks and tiles are masked.
     const int32_t* seq_state;
+    int32_t kg_shift;           // log2(G / 32): scales and zero-points are stored once per group (keys: row tile >> kg_shift;
+                                // values: 4 >> kg_shift entries per token); > 0 runs on instantiations of its own
     int32_t head_groups;        // > 1: runs of rep_here (4 or 8) query heads per kv-head served as units of one launch (matrix-core family)
     int32_t ragged_min_tiles;   // with seq_state: the fewest all-quantised tiles any sequence has (host knowledge)
     // Host side only (two-launch form): the residual flush of this decode step, to be carried out by

@@ -133,8 +133,7 @@ __device__ __forceinline__ void word_coords(int wd, int bit, int& lane, int& u, 
 }
 
 // One workgroup quantises one key group: TG tiles of 32 tokens (G = 32 * TG tokens per group).
-// Scale and zero-point rows are stored once per tile, i.e. replicated TG times: the decode kernels
-// read them at tile granularity whatever G is.
+// Scale and zero-point rows are stored once per group (row (tile / TG) of the arrays).
 // (A device function so that it can also run as a role of a wider launch: group g of kv-head h of
 // batch entry b; 256 threads work, any further threads of the workgroup only keep the barriers.)
 template <int BITS, int TG>
@@ -195,9 +194,9 @@ __device__ __forceinline__ void quantize_key_block(const QuantKeyParams& p, int 
             hi = fmaxf(hi, __half2float(phi[tq * kHeadDim + tid]));
         }
         const __half s16 = __float2half_rn((hi - lo) / levels);
-#pragma unroll
-        for (int ti = 0; ti < TG; ++ti) {
-            const int64_t o = (unit * p.cap_tiles + dst_tile + ti) * kHeadDim + tid;
+        {
+            // one row of scales / zero-points per group (dst_tile is a multiple of TG, and so is cap_tiles)
+            const int64_t o = (unit * p.cap_tiles + dst_tile) / TG * kHeadDim + tid;
             p.scale[o] = s16;
             p.zero[o] = __float2half_rn(lo);
         }
@@ -331,9 +330,8 @@ __device__ __forceinline__ void quantize_value_block(const QuantValueParams& p, 
         const std::integral_constant<int, 0x141> mirror8{};
         lo = fminf(lo, dpp(lo, xor1));
         hi = fmaxf(hi, dpp(hi, xor1));
-        // G = 64 or 128 channels per group: combine 2 or 4 neighbouring 32-channel blocks; every
-        // block then stores the group's scale and zero-point (replicated at 32-channel granularity,
-        // which is what the decode kernels read)
+        // G = 64 or 128 channels per group: combine 2 or 4 neighbouring 32-channel blocks (every block
+        // then holds the group's minimum and maximum; the first one stores its scale and zero-point)
         if (p.group_blocks >= 2) { lo = fminf(lo, dpp(lo, xor2)); hi = fmaxf(hi, dpp(hi, xor2)); }
         if (p.group_blocks >= 4) { lo = fminf(lo, dpp(lo, mirror8)); hi = fmaxf(hi, dpp(hi, mirror8)); }
         if (part == 0) sh_mm[t][cg] = make_float2(lo, hi);
@@ -347,9 +345,12 @@ __device__ __forceinline__ void quantize_value_block(const QuantValueParams& p, 
         if (t >= lo_tok && t < hi_tok) {
             const float2 mm = sh_mm[t][cg];
             const __half s16 = __float2half_rn((mm.y - mm.x) / levels);
-            const int64_t o = ((unit * p.cap_tiles + dst_tile) * kTileTokens + t) * 4 + cg;
-            p.scale[o] = s16;
-            p.zero[o] = __float2half_rn(mm.x);
+            // one entry per group: 4 / group_blocks of them per token, written by the group's first block
+            if (cg % p.group_blocks == 0) {
+                const int64_t o = ((unit * p.cap_tiles + dst_tile) * kTileTokens + t) * (4 / p.group_blocks) + cg / p.group_blocks;
+                p.scale[o] = s16;
+                p.zero[o] = __float2half_rn(mm.x);
+            }
             const GroupConst gc = group_const(mm.x, __half2float(s16));
             sh_g[t][cg] = gc;
             my_tol = gc.tol;

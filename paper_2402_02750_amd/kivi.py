@@ -199,10 +199,10 @@ class Cache:
         buf = self.buffers[name]
         if name in ("k_codes", "v_codes"):
             return buf.view(torch.int32).view(*units, tiles, 32 * 128 * l.bits // 32)
-        if name in ("k_scale", "k_zero"):
-            return buf.view(torch.float16).view(*units, tiles, 128)
-        if name in ("v_scale", "v_zero"):
-            return buf.view(torch.float16).view(*units, l.cap_q_tokens, 4)
+        if name in ("k_scale", "k_zero"):       # one row per group of G tokens
+            return buf.view(torch.float16).view(*units, l.cap_q_tokens // l.group, 128)
+        if name in ("v_scale", "v_zero"):       # one entry per group of G channels
+            return buf.view(torch.float16).view(*units, l.cap_q_tokens, 128 // l.group)
         return buf.view(torch.float16).view(*units, l.cap_r_tokens, 128)
 
 

@@ -54,16 +54,13 @@ def compare_quantized_state(cache, oc: ko.StreamingCache, heads=None):
         return torch.stack([t[b, h] for b, h in heads])[:, None].cpu().numpy()
 
     nkt, nvt = oc.n_kq // 32, (oc.n_vq + 31) // 32
-    # the library stores scales and zero-points per 32-token tile / 32-channel block whatever G is:
-    # a group of G = 32 * rep_g tokens (channels) has its pair replicated rep_g times
-    rep_g = cache.layout.group // 32
+    # scales and zero-points: one per group (keys: a row per G tokens; values: 128 / G entries per token)
+    nkg = oc.n_kq // cache.layout.group
     if nkt:
         got = pick(cache.view("k_codes")[:, :, :nkt]).view(np.uint32)
         assert np.array_equal(got, ko.pack_key_codes(oc.k_codes, bits)), "key codes differ"
-        assert np.array_equal(pick(cache.view("k_scale")[:, :, :nkt]).view(np.uint16),
-                              np.repeat(oc.k_scale, rep_g, axis=2).view(np.uint16))
-        assert np.array_equal(pick(cache.view("k_zero")[:, :, :nkt]).view(np.uint16),
-                              np.repeat(oc.k_zero, rep_g, axis=2).view(np.uint16))
+        assert np.array_equal(pick(cache.view("k_scale")[:, :, :nkg]).view(np.uint16), oc.k_scale.view(np.uint16))
+        assert np.array_equal(pick(cache.view("k_zero")[:, :, :nkg]).view(np.uint16), oc.k_zero.view(np.uint16))
     if oc.n_vq:
         got = pick(cache.view("v_codes")[:, :, :nvt]).view(np.uint32)
         pad = nvt * 32 - oc.n_vq
@@ -74,10 +71,8 @@ def compare_quantized_state(cache, oc: ko.StreamingCache, heads=None):
                                     np.zeros(codes.shape[:2] + (pad, 128), np.uint16)], axis=2)
             got = got & ko.pack_value_codes(valid, bits)
         assert np.array_equal(got, ko.pack_value_codes(codes, bits)), "value codes differ"
-        assert np.array_equal(pick(cache.view("v_scale")[:, :, :oc.n_vq]).view(np.uint16),
-                              np.repeat(oc.v_scale, rep_g, axis=3).view(np.uint16))
-        assert np.array_equal(pick(cache.view("v_zero")[:, :, :oc.n_vq]).view(np.uint16),
-                              np.repeat(oc.v_zero, rep_g, axis=3).view(np.uint16))
+        assert np.array_equal(pick(cache.view("v_scale")[:, :, :oc.n_vq]).view(np.uint16), oc.v_scale.view(np.uint16))
+        assert np.array_equal(pick(cache.view("v_zero")[:, :, :oc.n_vq]).view(np.uint16), oc.v_zero.view(np.uint16))
     for name, start, n, ref in (("k_resid", c.k_r_start, c.n_kr, oc.k_resid),
                                 ("v_resid", c.v_r_start, c.n_vr, oc.v_resid)):
         if n:

@@ -50,6 +50,11 @@ def test_cache_sizes_and_workspace(lib):
     assert s.k_scale == s.k_zero == units * 8 * 128 * 2
     assert s.v_scale == s.v_zero == units * 256 * 4 * 2
     assert s.k_resid == s.v_resid == units * 96 * 128 * 2
+    # one scale / zero-point pair per group: G = 128 stores a quarter of what G = 32 does
+    s128 = kivi.kivi_cache_sizes(kivi.make_layout(2, 4, 2, 2, 128, 256, 384, group=128))
+    assert s128.k_scale == s128.k_zero == units * 2 * 128 * 2
+    assert s128.v_scale == s128.v_zero == units * 256 * 1 * 2
+    assert s128.k_codes == s.k_codes
     l4 = _layout(bits=4)
     assert kivi.kivi_cache_sizes(l4).k_codes == units * 8 * 2048
     assert kivi.kivi_decode_workspace_bytes(l) >= 2 * 4 * 3 * 130 * 4

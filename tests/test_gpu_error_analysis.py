@@ -27,16 +27,14 @@ def _hip_fake_quantize(x: np.ndarray, bits: int, group: int, direction: str) -> 
         kivi.kivi_quantize_key_groups(layout, xt, n, cache)
         torch.cuda.synchronize()
         codes = ko.unpack_key_codes(cache.view("k_codes").cpu().numpy().view(np.uint32), bits)
-        rep_g = group // 32     # the library stores a group's pair once per 32-token tile
-        scale = cache.view("k_scale").cpu().numpy()[:, :, ::rep_g]
-        zero = cache.view("k_zero").cpu().numpy()[:, :, ::rep_g]
+        scale = cache.view("k_scale").cpu().numpy()       # one row per group of `group` tokens
+        zero = cache.view("k_zero").cpu().numpy()
         return ko.dequantize_key(codes, scale, zero, group)[0, 0]
     kivi.kivi_quantize_value_tokens(layout, xt, n, cache)
     torch.cuda.synchronize()
     codes = ko.unpack_value_codes(cache.view("v_codes").cpu().numpy().view(np.uint32), bits)
-    rep_g = group // 32
-    scale = cache.view("v_scale").cpu().numpy()[:, :, :, ::rep_g]
-    zero = cache.view("v_zero").cpu().numpy()[:, :, :, ::rep_g]
+    scale = cache.view("v_scale").cpu().numpy()           # one entry per group of `group` channels
+    zero = cache.view("v_zero").cpu().numpy()
     return ko.dequantize_value(codes, scale, zero, group)[0, 0]
 
 
