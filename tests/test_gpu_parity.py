@@ -68,6 +68,16 @@ def test_grouped_query(path, bits, rep):
     _run_case(w, 6000, kivi.KIVI_FLUSH_ALG1, path, heads=[(0, 1), (1, 0)])
 
 
+@pytest.mark.parametrize("bits,group,batch,n_kv,length", [(2, 64, 256, 8, 330), (4, 128, 256, 8, 520)], ids=["G64", "G128"])
+def test_many_units_larger_groups(bits, group, batch, n_kv, length):
+    """The one-unit-per-wavefront kernel with G = 64 / 128 (one scale / zero-point pair per group in
+    memory): every unit against the oracle, state bit-exact."""
+    w = scaled(CONFIGS["stream"], name="many_units_g", batch=batch, n_q_heads=n_kv, n_kv_heads=n_kv, bits=bits,
+               group=group, residual=group, seed=2700 + group)
+    print(f"case many_units_g bits={bits} G={group} units={batch * n_kv} L={length}", flush=True)
+    _run_case(w, length, kivi.KIVI_FLUSH_WINDOW, kivi.KIVI_DECODE_AUTO)
+
+
 @pytest.mark.parametrize("bits,rep,batch,n_kv,length", [
     (2, 1, 256, 8, 300),      # 2048 units = one per resident wavefront; 7 all-quantised tiles (a short last group of 3)
     (4, 1, 272, 8, 200),      # 2176 units: a second, sparse round of units; 4 tiles
