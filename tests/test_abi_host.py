@@ -270,6 +270,16 @@ def test_decode_plan(lib):
     # vector-ALU family: decode + merge
     p = plan(16, 32, 32, 2, 3968, 128, path=kivi.KIVI_DECODE_VALU)
     assert (p.family, p.launches) == (kivi.KIVI_DECODE_VALU, 2)
+    # more than 8 query heads per kv-head (multi-query attention): runs of 4 heads as units of one
+    # launch in the single-launch form; one pass per 8 heads in the two-launch form and the vector-ALU family
+    p = plan(16, 71, 1, 2, 3968, 128)
+    assert (p.launches, p.units_per_kv_head) == (1, 18)
+    p = plan(4, 128, 8, 4, 3968, 128)
+    assert (p.launches, p.units_per_kv_head) == (1, 4)
+    p = plan(16, 71, 1, 2, 3968, 128, path=kivi.KIVI_DECODE_MFMA_TWO)
+    assert (p.launches, p.units_per_kv_head) == (18, 1)
+    p = plan(16, 71, 1, 2, 3968, 128, path=kivi.KIVI_DECODE_VALU)
+    assert (p.launches, p.units_per_kv_head) == (10, 1)
     bad = kivi.kivi_decode_plan_t()
     l = _layout()
     assert lib.kivi_decode_plan(ctypes.byref(l), None, ctypes.byref(bad)) == kivi.KIVI_ERR_INVALID_ARG
