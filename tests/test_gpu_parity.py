@@ -304,6 +304,29 @@ def test_random_shapes(seed):
     _run_case(w, length, policy, path, heads=heads)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_large_batches(seed):
+    """Seeded random layouts with hundreds to thousands of (batch, kv-head) units (short contexts):
+    the two-launch form with the one-unit-per-wavefront kernel where the unit count fits it, the
+    shared-unit form where it does not, G = 32 / 64 / 128; sampled units against the oracle."""
+    rng = np.random.default_rng(9500 + seed)
+    group = int(rng.choice([32, 32, 64, 128]))
+    residual = group * int(rng.integers(1, 256 // group + 1))
+    rep = int(rng.choice([1, 1, 2, 3, 4, 8]))
+    n_kv = int(rng.choice([2, 4, 8]))
+    batch = int(rng.integers(256, 620))
+    w = scaled(CONFIGS["llama7b"], name=f"randbig{seed}", batch=batch, n_q_heads=n_kv * rep, n_kv_heads=n_kv,
+               bits=int(rng.choice([2, 4])), group=group, residual=residual, seed=12500 + seed)
+    length = int(rng.integers(1, 700))
+    policy = kivi.KIVI_FLUSH_WINDOW if rng.integers(0, 3) else kivi.KIVI_FLUSH_ALG1
+    path = [kivi.KIVI_DECODE_AUTO, kivi.KIVI_DECODE_MFMA_TWO, kivi.KIVI_DECODE_MFMA_ONE][int(rng.integers(0, 3))]
+    all_heads = [(b, h) for b in range(w.batch) for h in range(w.n_kv_heads)]
+    heads = [all_heads[i] for i in rng.choice(len(all_heads), size=6, replace=False)]
+    print(f"case random large seed={seed} b={w.batch} kv={n_kv} rep={rep} bits={w.bits} G={group} R={residual} "
+          f"L={length} policy={policy} path={path}", flush=True)
+    _run_case(w, length, policy, path, heads=heads)
+
+
 @pytest.mark.parametrize("group", [32, 128])
 @pytest.mark.parametrize("bits", [2, 4])
 @pytest.mark.parametrize("kind", workloads.ADVERSARIAL_KINDS)
