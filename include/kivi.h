@@ -298,8 +298,10 @@ int kivi_batch_slice(const kivi_layout_t* layout, const kivi_cache_t* cache, int
  * kv-head), and at least one sequence has quantised tokens.  The fp16 rows of all sequences run in
  * one launch (which also appends the step's new tokens), the all-quantised parts in a second; both
  * read each sequence's counters from a copy in the workspace, and the shorter sequences' share of
- * the work partition is skipped.  A step adds one launch per run of equal sequences that flush in
- * it (a sequence flushes every G-th step).
+ * the work partition is skipped (where that share is large, or the batch holds as many (batch,
+ * kv-head) units as the chip holds wavefronts, the second launch divides the tokens that are there
+ * evenly over the wavefronts instead).  A step adds one launch per run of equal sequences that flush
+ * in it (a sequence flushes every G-th step).
  *   Otherwise (another policy or family, empty slots, sequences without fp16 rows) the batch is
  * walked in runs of consecutive entries with equal state and each run is one call of the uniform
  * entry point on that part of the batch (same stream, same workspace): B different lengths take B

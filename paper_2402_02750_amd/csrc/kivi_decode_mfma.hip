@@ -1214,7 +1214,14 @@ int resident_workgroups() {
 // unit ahead): no barrier, no cross-wavefront merge, no device-scope traffic; leaving a unit is
 // a reduction inside the wavefront and the output store.  Same tile arithmetic (the device functions
 // above), same running-maximum softmax, same merge with the part of the fp16-row launch.
-template <int BITS, int REP, int OCC, bool CS = false>
+// SLICES: instead of whole units in a stride, a wavefront walks a SLICE of the unit-major axis of
+// four-tile groups (first unit, first group, number of groups: p.wave_desc, made by the host so that
+// all slices are equally long whatever the sequences' lengths are).  A unit that several slices touch
+// gets one part per slice in the workspace (device-scope stores, then the unit's counter); the
+// wavefront that finds the counter complete merges the parts and the fp16-row launch's part and
+// writes the output -- all inside wavefronts, still no barrier.  p.unit_parts holds, per unit, the
+// first slice that touches it and the number of slices that do.
+template <int BITS, int REP, int OCC, bool CS = false, bool SLICES = false>
 __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParams p) {
     constexpr int kSlots = 4;
     constexpr int kStage = REP > 2 ? 1 : 2;
@@ -1243,7 +1250,14 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
         return p.seq_state ? __builtin_amdgcn_readfirstlane(p.seq_state[4 * (u / p.n_kv_heads)]) / kTileTokens : p.plan.tiles_a;
     };
     const int row_stride = p.plan.n_splits();           // workspace rows per (batch, query head); row 0: the fp16-row launch's part
-    if (gw >= units) return;                            // whole wavefronts leave; the kernel has no barrier
+    if (gw >= (SLICES ? p.n_slices : units)) return;    // whole wavefronts leave; the kernel has no barrier
+    // this wavefront's slice (SLICES): first unit, first group in it, groups to do
+    int sl_unit = 0, sl_group = 0, sl_count = 0;
+    if constexpr (SLICES) {
+        sl_unit = __builtin_amdgcn_readfirstlane(p.wave_desc[4 * gw + 0]);
+        sl_group = __builtin_amdgcn_readfirstlane(p.wave_desc[4 * gw + 1]);
+        sl_count = __builtin_amdgcn_readfirstlane(p.wave_desc[4 * gw + 2]);
+    }
 
     auto first_q_head = [&](int u) -> int { return (u % p.n_kv_heads) * rep_total + p.q_head0; };
     auto batch_of = [&](int u) -> int { return u / p.n_kv_heads; };
@@ -1253,7 +1267,8 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
     half8 zf[4];
     // the group whose data is being requested ("next"); requests are unconditional (past the end they
     // re-read tile 0 of unit 0) so that the compiler counts the outstanding loads exactly
-    int nx_u = gw, nx_g = 0, nx_tiles = tiles_of(gw);
+    int nx_u = SLICES ? sl_unit : gw, nx_g = SLICES ? sl_group : 0, nx_tiles = tiles_of(nx_u);
+    int nx_left = sl_count;                             // SLICES: groups of the slice not requested yet
     bool nx_ok = true;
     auto next_tile = [&](int slot) -> int64_t {
         return nx_ok ? (int64_t)nx_u * p.cap_tiles + min(nx_g * kSlots + slot, nx_tiles - 1) : 0;
@@ -1263,11 +1278,21 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
         return nx_ok ? (((int64_t)nx_u * p.cap_tiles) >> kg) + (min(nx_g * kSlots + slot, nx_tiles - 1) >> kg) : 0;
     };
     auto advance_next = [&]() {
-        if (++nx_g * kSlots >= nx_tiles) {
-            nx_g = 0;
-            nx_u += n_waves;
-            nx_ok = nx_u < units;
-            nx_tiles = nx_ok ? tiles_of(nx_u) : 1;
+        if constexpr (SLICES) {
+            nx_ok = --nx_left > 0;
+            if (++nx_g * kSlots >= nx_tiles) {
+                nx_g = 0;
+                ++nx_u;
+                nx_ok = nx_ok && nx_u < units;
+                nx_tiles = nx_ok ? tiles_of(nx_u) : 1;
+            }
+        } else {
+            if (++nx_g * kSlots >= nx_tiles) {
+                nx_g = 0;
+                nx_u += n_waves;
+                nx_ok = nx_u < units;
+                nx_tiles = nx_ok ? tiles_of(nx_u) : 1;
+            }
         }
     };
     auto request_zero_rows = [&]() {
@@ -1353,15 +1378,21 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
         wave_lds_sync();
     };
 
-    request_unit(gw);
+    request_unit(SLICES ? sl_unit : gw);
     request_zero_rows();
 #pragma unroll
     for (int i = 0; i < kSlots; ++i) request_key_slot(i);
 #pragma unroll
     for (int i = 0; i < kSlots; ++i) request_value_slot(i);
 
-    for (int u = gw; u < units; u += n_waves) {
+    int g_first = sl_group, left = sl_count;
+    for (int u = SLICES ? sl_unit : gw; SLICES ? left > 0 : u < units; u += SLICES ? 1 : n_waves) {
         // ---- enter the unit: query operands of this wavefront ----
+        int first_slice = 0, n_parts = 1;               // SLICES: the slices that touch this unit
+        if constexpr (SLICES) {
+            first_slice = __builtin_amdgcn_readfirstlane(p.unit_parts[2 * u + 0]);
+            n_parts = __builtin_amdgcn_readfirstlane(p.unit_parts[2 * u + 1]);
+        }
         float um[kIdx], ul[kIdx], uo[kIdx];              // the fp16-row launch's part of this unit
 #pragma unroll
         for (int k = 0; k < kIdx; ++k) {
@@ -1375,7 +1406,7 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
             um[k] = pre_m[k]; ul[k] = pre_l[k]; uo[k] = pre_o[k];
         }
         wave_lds_sync();
-        request_unit(u + n_waves);                      // one unit ahead
+        request_unit(SLICES ? u + 1 : u + n_waves);     // one unit ahead
         {
             const float pf = inv_pos_factor<BITS>(lane & 3);
 #pragma unroll
@@ -1394,7 +1425,13 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
         }
 
         const int tiles = tiles_of(u);
-        for (int g = 0; g * kSlots < tiles; ++g) {
+        const int g_lo = SLICES ? g_first : 0;
+        const int g_hi = SLICES ? min((tiles + kSlots - 1) / kSlots, g_first + left) : (tiles + kSlots - 1) / kSlots;
+        if constexpr (SLICES) {
+            left -= g_hi - g_lo;
+            g_first = 0;
+        }
+        for (int g = g_lo; g < g_hi; ++g) {
             const int cnt = min(kSlots, tiles - g * kSlots);          // tiles of this group
             advance_next();                                             // the requests below are for the group after this one
             // key z-terms of the four slots: one 16x16x128 product
@@ -1462,19 +1499,78 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
         }
         wave_lds_sync();
         const int64_t row0 = (int64_t)batch_of(u) * p.n_q_heads + first_q_head(u);
+        if (!SLICES || n_parts == 1) {
 #pragma unroll
-        for (int k = 0; k < kIdx; ++k) {
-            const int hh = k >> 1, c = lane + 64 * (k & 1);
-            if (hh < rep) {
-                float mm = m_run[hh], ll = l_w[hh];
-                float oo = fmaf(join_hi_lo(wl.lr[2 * hh][c], wl.lr[2 * hh + 1][c]), kUnscale, sm_zs[wave][hh][c >> 5]);
-                if (um[k] > -INFINITY) {                 // the fp16-row launch's part (the window is never empty in this form)
-                    const float mn = fmaxf(mm, um[k]);
-                    const float f_old = __expf(mm - mn), f_new = __expf(um[k] - mn);
-                    ll = fmaf(ll, f_old, ul[k] * f_new);
-                    oo = fmaf(oo, f_old, uo[k] * f_new);
+            for (int k = 0; k < kIdx; ++k) {
+                const int hh = k >> 1, c = lane + 64 * (k & 1);
+                if (hh < rep) {
+                    float mm = m_run[hh], ll = l_w[hh];
+                    float oo = fmaf(join_hi_lo(wl.lr[2 * hh][c], wl.lr[2 * hh + 1][c]), kUnscale, sm_zs[wave][hh][c >> 5]);
+                    if (um[k] > -INFINITY) {                 // the fp16-row launch's part (the window is never empty in this form)
+                        const float mn = fmaxf(mm, um[k]);
+                        const float f_old = __expf(mm - mn), f_new = __expf(um[k] - mn);
+                        ll = fmaf(ll, f_old, ul[k] * f_new);
+                        oo = fmaf(oo, f_old, uo[k] * f_new);
+                    }
+                    p.out[(row0 + hh) * kHeadDim + c] = oo / ll;
                 }
-                p.out[(row0 + hh) * kHeadDim + c] = oo / ll;
+            }
+        } else {
+            // several slices share the unit: this one's part goes to the workspace (slot 0 is the fp16-row
+            // launch's), published as in decode_mfma_kernel: device-scope stores, the wait for their
+            // acknowledgement, then the counter; whoever completes the count merges
+            const int slot = 1 + gw - first_slice;
+#pragma unroll
+            for (int k = 0; k < kIdx; ++k) {
+                const int hh = k >> 1, c = lane + 64 * (k & 1);
+                if (hh < rep) {
+                    const float oo = fmaf(join_hi_lo(wl.lr[2 * hh][c], wl.lr[2 * hh + 1][c]), kUnscale, sm_zs[wave][hh][c >> 5]);
+                    const int64_t prow = (row0 + hh) * row_stride + slot;
+                    device_store(p.part_o + prow * kHeadDim + c, oo);
+                    if (c == 0) {
+                        device_store(p.part_ml + prow * 2 + 0, m_run[hh]);
+                        device_store(p.part_ml + prow * 2 + 1, l_w[hh]);
+                    }
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            int done = 0;
+            if (lane == 0) done = __hip_atomic_fetch_add(p.counters + u, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            done = __builtin_amdgcn_readfirstlane(done);
+            if (done == n_parts - 1) {
+#pragma unroll
+                for (int k = 0; k < kIdx; ++k) {
+                    const int hh = k >> 1, c = lane + 64 * (k & 1);
+                    if (hh < rep) {
+                        const int64_t prow = (row0 + hh) * row_stride;
+                        float mm = um[k], ll = ul[k], oo = uo[k];          // slot 0: written by the previous launch
+                        if (!(mm > -INFINITY)) { mm = -INFINITY; ll = 0.f; oo = 0.f; }
+                        // eight parts at a time: the device-scope loads of a batch are all issued before
+                        // the first is used (each is a trip to memory, not to a cache)
+                        for (int i0 = 1; i0 <= n_parts; i0 += 8) {
+                            float mv[8], lv[8], ov[8];
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                const int i = min(i0 + j, n_parts);
+                                mv[j] = device_load(p.part_ml + (prow + i) * 2 + 0);
+                                lv[j] = device_load(p.part_ml + (prow + i) * 2 + 1);
+                                ov[j] = device_load(p.part_o + (prow + i) * kHeadDim + c);
+                            }
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                if (i0 + j <= n_parts && mv[j] > -INFINITY) {
+                                    const float mn = fmaxf(mm, mv[j]);
+                                    const float f_old = __expf(mm - mn), f_new = __expf(mv[j] - mn);   // mm = -inf: f_old = 0
+                                    ll = fmaf(ll, f_old, lv[j] * f_new);
+                                    oo = fmaf(oo, f_old, ov[j] * f_new);
+                                    mm = mn;
+                                }
+                            }
+                        }
+                        p.out[(row0 + hh) * kHeadDim + c] = oo / ll;
+                    }
+                }
+                if (lane == 0) __hip_atomic_store(p.counters + u, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         wave_lds_sync();                                 // this wavefront's LDS is reused by its next unit
@@ -1482,7 +1578,7 @@ __global__ __launch_bounds__(256, OCC) void decode_wave_units_kernel(DecodeParam
 }
 
 // Wavefronts the device holds at once for decode_wave_units_kernel (per device, as above).
-template <int BITS, int REP, int OCC, bool CS = false>
+template <int BITS, int REP, int OCC, bool CS = false, bool SLICES = false>
 int resident_wave_unit_workgroups() {
     static std::atomic<int> cached[kMaxDevices];
     int dev = 0, cus = 0, per_cu = 0;
@@ -1493,7 +1589,7 @@ int resident_wave_unit_workgroups() {
         if (c > 0) return c;
     }
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_wave_units_kernel<BITS, REP, OCC, CS>, 256, 0) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_wave_units_kernel<BITS, REP, OCC, CS, SLICES>, 256, 0) != hipSuccess ||
         cus <= 0 || per_cu <= 0)
         return 256 * OCC;
     if (keep) cached[dev].store(cus * per_cu, std::memory_order_relaxed);
@@ -1551,6 +1647,14 @@ hipError_t launch_two(DecodeParams p, hipStream_t stream) {
     p.total_cost = total_a;
     // One unit per wavefront where that fills the chip evenly: at least as many units as resident
     // wavefronts, and the last round of units at most 12 % short of a full one.
+    if constexpr (REP <= 4 && !CS) {
+        if (p.wave_desc != nullptr) {
+            // equally long slices of the unit-major group axis, one per wavefront (tables made by the host)
+            if (p.n_slices < 1 || p.unit_parts == nullptr) return hipErrorInvalidValue;
+            decode_wave_units_kernel<BITS, REP, OCC, false, true><<<(p.n_slices + 3) / 4, 256, 0, stream>>>(p);
+            return hipGetLastError();
+        }
+    }
     if constexpr (REP <= 4) {
         if (!p.seq_state || (!CS && p.ragged_min_tiles >= 1)) {
             const int64_t waves = 4 * (int64_t)resident_wave_unit_workgroups<BITS, REP, OCC, CS>();
@@ -1639,6 +1743,15 @@ hipError_t launch_decode_mfma(const DecodeParams& p, hipStream_t stream) {
                                : launch_one<V::bits, V::rep, V::slots, V::occ>(p, stream);
     });
     return e;
+}
+
+int wave_slices_resident(int bits, int rep) {
+    int waves = 0;
+    with_variant(bits, rep, [&](auto v) {
+        using V = decltype(v);
+        if constexpr (V::rep <= 4) waves = 4 * resident_wave_unit_workgroups<V::bits, V::rep, V::occ, false, true>();
+    });
+    return waves;
 }
 
 MfmaGeometry mfma_geometry(int bits, int rep) {

@@ -114,6 +114,12 @@ struct DecodeParams {
     int32_t kg_shift;           // log2(G / 32): scales and zero-points are stored once per group (keys: row tile >> kg_shift;
                                 // values: 4 >> kg_shift entries per token); > 0 runs on instantiations of its own
     int32_t head_groups;        // > 1: runs of rep_here (4 or 8) query heads per kv-head served as units of one launch (matrix-core family)
+    // Two-launch form, second launch as equally long slices of the unit-major axis of four-tile groups
+    // (device arrays made by the host; null: not used): wave_desc[4 s] = {first unit, first group in it,
+    // groups, 0} of slice s; unit_parts[2 u] = {first slice touching unit u, slices touching it}.
+    const int32_t* wave_desc;
+    const int32_t* unit_parts;
+    int32_t n_slices;
     int32_t ragged_min_tiles;   // with seq_state: the fewest all-quantised tiles any sequence has (host knowledge)
     // Host side only (two-launch form): the residual flush of this decode step, to be carried out by
     // extra workgroups of the fp16-row launch instead of a launch of its own; null otherwise.
@@ -146,5 +152,7 @@ hipError_t launch_stream_read(const void* src, size_t bytes, uint32_t* sink, hip
 // that serves (bits, query heads per kv-head); the split planner and the kernel must agree on both.
 struct MfmaGeometry { int chunk_tiles, resident_workgroups; };
 MfmaGeometry mfma_geometry(int bits, int rep);
+// wavefronts the device holds of the sliced form of decode_wave_units_kernel (0: no instantiation for the shape)
+int wave_slices_resident(int bits, int rep);
 
 }  // namespace kivi

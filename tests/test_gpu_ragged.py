@@ -186,3 +186,57 @@ def test_ragged_wide_batches_and_groups(batch, n_q_heads, n_kv_heads):
     for b in range(w.batch):
         worst = max(worst, gh.check_close(got[b:b + 1], oracles[b].attention(q[b:b + 1], w.softmax_scale), f"seq {b} (n={prompts[b]})"))
     print(f"case raggedwide: worst abs err {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("bits,rep", [(2, 1), (4, 2), (2, 4)])
+def test_ragged_very_different_lengths(bits, rep):
+    """768 units whose sequences run from 40 to 6000 tokens: the padded plan would waste more than
+    14 000 four-tile group steps, so the second launch runs as equally long slices of the unit-major
+    axis, one per wavefront, with the units that several slices share merged through the workspace.
+    Two decoding steps and an attention call, every sequence against an oracle cache of its own."""
+    torch = gh.require_gpu()
+    n_seq, n_kv = 48, 16
+    rng = np.random.default_rng(40 + bits + rep)
+    prompts = [int(x) for x in rng.integers(40, 6000, size=n_seq)]
+    prompts[0], prompts[1], prompts[-1] = 6000, 97, 5999
+    groups = [-(-((n - 64) // 32) // 4) for n in prompts]
+    assert n_seq * n_kv * max(groups) - n_kv * sum(groups) >= 14000        # the condition for the sliced form
+    w = scaled(CONFIGS["stream"], name="raggedslices", batch=n_seq, n_q_heads=n_kv * rep, n_kv_heads=n_kv, bits=bits,
+               residual=64, prompt=0, decode_steps=0, seed=909 + bits + rep)
+    steps = 2
+    total = max(prompts) + steps
+    k, v = workloads.keys(w, total), workloads.values(w, total)
+    layout = kivi.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.bits, w.residual, gh.round_up(total, 32), 128)
+    cache = kivi.Cache(layout)
+    states = kivi.make_states(w.batch)
+    kt, vt = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    oracles = []
+    print(f"case raggedslices bits={bits} rep={rep}: per-sequence prefill", flush=True)
+    for b, n in enumerate(prompts):
+        oc = ko.StreamingCache(1, w.n_kv_heads, 128, w.bits, w.group, w.residual, "window")
+        sl = kivi.CacheSlice(cache, b, 1)
+        kivi.kivi_prefill(sl.layout, kt[b:b + 1], vt[b:b + 1], n, sl, kivi.KIVI_FLUSH_WINDOW)
+        states[b] = sl.state()
+        oc.prefill(k[b:b + 1, :, :n], v[b:b + 1, :, :n])
+        oracles.append(oc)
+    out = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    lengths = list(prompts)
+    worst = 0.0
+    for step in range(steps + 1):
+        q = workloads.queries(w, step)
+        if step < steps:
+            k_new = torch.stack([kt[b, :, lengths[b]] for b in range(w.batch)]).contiguous()
+            v_new = torch.stack([vt[b, :, lengths[b]] for b in range(w.batch)]).contiguous()
+            kivi.kivi_decode_step_ragged(layout, cache, states, k_new, v_new, torch.from_numpy(q).cuda(),
+                                         w.softmax_scale, out, kivi.KIVI_FLUSH_WINDOW)
+            for b in range(w.batch):
+                oracles[b].append(k[b:b + 1, :, lengths[b]], v[b:b + 1, :, lengths[b]])
+                lengths[b] += 1
+        else:
+            kivi.kivi_decode_attention_ragged(layout, cache, states, torch.from_numpy(q).cuda(), w.softmax_scale, out)
+        torch.cuda.synchronize()
+        assert kivi.kivi_decode_launches_ragged(layout, states) == 2
+        got = out.cpu().numpy()
+        for b in range(w.batch):
+            worst = max(worst, gh.check_close(got[b:b + 1], oracles[b].attention(q[b:b + 1], w.softmax_scale), f"step {step} seq {b}"))
+        print(f"case raggedslices: step {step} ok, worst abs err {worst:.3e}", flush=True)
