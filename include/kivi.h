@@ -13,14 +13,16 @@
  *     launched and no cache field is changed;
  *   - work is enqueued on the caller's HIP stream (`stream` is a hipStream_t passed as void*;
  *     NULL = the default stream) and the call returns without synchronising;
- *   - the library never allocates or frees memory: all buffers, including the attention
+ *   - the library never allocates or frees device memory: all buffers, including the attention
  *     workspace, belong to the caller (kivi_decode_attention_static is the one exception: its
  *     workspace is an array inside the library).  The only state it keeps between calls is, per
- *     device, the answer of one occupancy query per kernel instantiation, and that array's address;
+ *     device, the answer of one occupancy query per kernel instantiation and that array's address,
+ *     and, per host thread, a small staging buffer (host memory) from which the ragged entry points
+ *     copy their per-sequence tables to the workspace;
  *   - pointers inside kivi_cache_t, `q`, `out`, `workspace` and the fp16 source tensors are DEVICE
  *     pointers, 16-byte aligned; the structs themselves and all counts live on the host;
- *   - the kernels work on batches of equal length; kivi_decode_step_ragged / kivi_decode_attention_ragged
- *     walk a batch of different lengths in runs of equal length.
+ *   - the uniform entry points work on batches of equal length; kivi_decode_step_ragged /
+ *     kivi_decode_attention_ragged serve batches whose sequences differ in length.
  *
  * Arithmetic contract of the quantiser (bit-exact between implementations)
  *   z = min over the group (an fp16 value, stored as is)
